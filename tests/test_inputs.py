@@ -1,0 +1,59 @@
+"""The seeded input generators: determinism, numpy/torch agreement, and the
+property that makes mis-routing visible (blocks differ when any index differs)."""
+import numpy as np
+import torch
+
+import iso_inputs as gen
+
+
+def test_numpy_and_torch_generators_agree_bitwise():
+    for kind, m in (("u32", 32), ("u32", 7), ("f32", 64), ("u32", 4096)):
+        a = gen.alltoall_send(3, 50, 5, m, kind)
+        b = gen.alltoall_send_torch(3, 50, 5, m, kind, rank_chunk=16).numpy()
+        assert a.dtype == np.uint8 and a.shape == (50, 5, m)
+        assert np.array_equal(a, b)
+        g = gen.allgather_send(3, 50, m, kind)
+        assert np.array_equal(g, gen.allgather_send_torch(3, 50, m, kind).numpy())
+    ranks = np.array([[5, 9], [0, 49]])
+    slots = np.array([[1, 2]])
+    a = gen.block_bytes(8, ranks, slots, 48)
+    b = gen.block_bytes_torch(8, torch.from_numpy(ranks), torch.from_numpy(slots), 48).numpy()
+    assert a.shape == (2, 2, 48) and np.array_equal(a, b)
+
+
+def test_rows_are_a_pure_function_of_their_indices():
+    full = gen.alltoall_send(9, 40, 6, 32)
+    part = gen.alltoall_send(9, 40, 6, 32, rank_lo=10, rank_hi=17)
+    assert np.array_equal(full[10:17], part)
+    assert not np.array_equal(full, gen.alltoall_send(10, 40, 6, 32))
+
+
+def test_every_block_and_every_word_is_distinct_enough():
+    a = gen.alltoall_send(1, 64, 8, 32).reshape(64 * 8, 32)
+    assert len({row.tobytes() for row in a}) == 64 * 8
+    w = a.view(np.uint32)
+    # first word alone already separates all (rank, slot) pairs (bijective stages)
+    assert len(set(w[:, 0].tolist())) == 64 * 8
+    # words inside a block are pairwise distinct
+    big = gen.alltoall_send(1, 2, 2, 4096).reshape(4, 4096).view(np.uint32)
+    for row in big:
+        assert len(set(row.tolist())) == row.size
+
+
+def test_f32_blocks_are_finite_and_in_range():
+    f = gen.alltoall_send(2, 16, 3, 1024, "f32").view(np.float32)
+    assert np.isfinite(f).all() and f.min() >= -1.0 and f.max() < 1.0
+    assert abs(float(f.mean())) < 0.05
+
+
+def test_config_table_matches_the_named_workloads():
+    c = gen.CONFIGS
+    assert [x.p for x in c] == [64, 32768, 65536, 262144, 32768]
+    assert [x.s for x in c] == [8, 26, 12, 26, 40]
+    assert [x.m for x in c] == [32, 256, 1024, 128, 4096]
+    assert c[3].m_sweep == (16, 64, 128)
+    c5 = c[4]
+    assert len(set(c5.offsets)) == 40 and all(any(v) for v in c5.offsets)
+    assert all(-3 <= x <= 3 for v in c5.offsets for x in v)
+    assert gen.random_distinct(5, -3, 3, 40, 1606_07676) == list(c5.offsets)
+    assert gen.get_config("2") is c[1] and gen.get_config(c[2].name) is c[2]
