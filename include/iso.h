@@ -1,0 +1,217 @@
+/*
+ * iso.h -- C ABI of libiso: isomorphic sparse all-to-all and allgather on a
+ * d-dimensional torus whose p processes are all virtual ranks resident in one
+ * GPU's memory (gfx950).
+ *
+ * The interface follows the paper's persistent interface (Section 2: the
+ * neighbourhood set-up call, the *_init calls, Iso_start, Iso_request_free;
+ * Section 7: the proposed Iso_wait), with the MPI objects replaced by plain
+ * arguments: torus dimension sizes, the flattened list of relative
+ * coordinates, the block size in bytes, device pointers and a HIP stream.
+ *
+ * Conventions
+ *   - Every function returns an int status: ISO_SUCCESS (0) or an ISO_ERR_*
+ *     code.  No exception or abort crosses this boundary.  On error the output
+ *     handle (if any) is left NULL.
+ *   - Ranks are row-major over (p_0..p_{d-1}), last dimension fastest.
+ *   - "host" / "device" below says where a pointer must live.  The caller owns
+ *     every buffer it passes; the library owns only its handles and, per
+ *     request, one small device table of block index maps (allocated in the
+ *     init call, freed in iso_request_free).
+ *   - A handle may be used from one host thread at a time.
+ */
+#ifndef ISO_H
+#define ISO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define ISO_MAX_DIMS 16          /* largest torus dimensionality accepted */
+
+enum iso_status {
+    ISO_SUCCESS       = 0,
+    ISO_ERR_ARG       = 1,       /* null / out-of-range / inconsistent argument            */
+    ISO_ERR_OVERLAP   = 2,       /* send, receive and workspace ranges are not disjoint     */
+    ISO_ERR_WORKSPACE = 3,       /* workspace smaller than iso_workspace_bytes() reports    */
+    ISO_ERR_HIP       = 4,       /* a HIP runtime call failed (see iso_last_hip_error)      */
+    ISO_ERR_NOMEM     = 5,       /* host allocation failed                                  */
+    ISO_ERR_TOO_LARGE = 6,       /* a size exceeds what the kernels index (see iso_*_init)  */
+    ISO_ERR_POINTER   = 7        /* a buffer is not device memory or its allocation is too
+                                    small for the range the collective touches             */
+};
+
+enum iso_op {
+    ISO_OP_ALLTOALL  = 0,        /* individual block per neighbour (Section 2)  */
+    ISO_OP_ALLGATHER = 1         /* same block to every neighbour (Section 2)   */
+};
+
+enum iso_algorithm {
+    /* Message-combining, torus-direct schedule (Section 5): one round per
+     * dimension j and distinct non-zero coordinate value v; one kernel launch
+     * per round.  All-to-all uses the alternating receive/intermediate buffer
+     * rule of Algorithm 1; allgather routes along the prefix trie of
+     * Section 3.2. */
+    ISO_ALG_COMBINED       = 0,
+    /* Same schedule, all rounds of one dimension issued as a single launch
+     * (they touch disjoint blocks; the k-ported remark of Section 3). */
+    ISO_ALG_COMBINED_BYDIM = 1,
+    /* Straightforward algorithm (first listing of Section 3): one exchange,
+     * here one launch, per neighbour; s launches. */
+    ISO_ALG_SX_ROUNDS      = 2,
+    /* The same s exchanges issued as a single launch. */
+    ISO_ALG_SX_FUSED       = 3
+};
+
+enum iso_buffer {                /* where a block sits during a schedule */
+    ISO_BUF_SEND = 0,
+    ISO_BUF_RECV = 1,
+    ISO_BUF_WORK = 2             /* intermediate buffer (all-to-all, Algorithm 1) or
+                                    temporary trie nodes (allgather) in the workspace */
+};
+
+enum iso_round_kind {
+    ISO_ROUND_SHIFT  = 0,        /* every entry moves along one dimension (per-entry distance) */
+    ISO_ROUND_SELF   = 1,        /* zero offset: same-rank copy send -> recv                   */
+    ISO_ROUND_VECTOR = 2         /* every entry moves by its full offset vector (s-exchange)   */
+};
+
+typedef struct iso_comm_s    *iso_comm_t;     /* torus + neighbourhood                    */
+typedef struct iso_plan_s    *iso_plan_t;     /* schedule for (comm, op, algorithm)       */
+typedef struct iso_request_s *iso_request_t;  /* schedule bound to buffers and block size */
+
+typedef struct {
+    int32_t d;                   /* dimensions                                             */
+    int32_t s;                   /* neighbours                                             */
+    int64_t p;                   /* processes = prod p_j                                   */
+    int32_t rounds;              /* torus-direct rounds: sum_j #distinct non-zero residues */
+    int32_t self_slots;          /* neighbours whose offset is 0 modulo the torus          */
+    int64_t alltoall_moves;      /* sum_i nnz(C^i): blocks moved per rank, all-to-all      */
+    int64_t allgather_moves;     /* blocks moved per rank, allgather (trie, chosen order)  */
+} iso_comm_info_t;
+
+typedef struct {
+    int32_t op, algorithm;
+    int32_t launches;            /* kernel launches per iso_start (= rounds of the plan)   */
+    int32_t work_slots;          /* blocks per rank held in the workspace                  */
+    int64_t entries;             /* block-moves per rank per collective (incl. self)       */
+    int32_t dim_order[ISO_MAX_DIMS]; /* allgather: order in which dimensions are routed    */
+} iso_plan_info_t;
+
+typedef struct {
+    int32_t kind;                /* enum iso_round_kind                                    */
+    int32_t dim;                 /* ISO_ROUND_SHIFT: dimension j; otherwise -1             */
+    int32_t n_entries;           /* k: blocks moved per rank in this launch                */
+    int32_t reserved;
+} iso_round_info_t;
+
+typedef struct {
+    int32_t src_buf, src_slot;   /* enum iso_buffer, block index inside that buffer's row  */
+    int32_t dst_buf, dst_slot;
+    int32_t shift;               /* SHIFT rounds: residue v in (0, p_j): the block comes
+                                    from the rank v steps back in `dim`; else 0            */
+    int32_t neighbor;            /* index i of the offset whose route this move belongs to
+                                    (allgather temporaries: -1); VECTOR rounds: source is
+                                    R (-) C^neighbor                                        */
+} iso_plan_entry_t;
+
+typedef struct {
+    int32_t op, algorithm;
+    int32_t launches;
+    int32_t vector_bytes;        /* width of the loads/stores chosen from alignment: 16..1 */
+    int64_t p, s;
+    uint64_t block_bytes;        /* m                                                       */
+    int64_t entries;             /* block-moves per rank                                    */
+    uint64_t bytes_read;         /* algorithmic bytes read per iso_start = entries*p*m      */
+    uint64_t bytes_written;      /* algorithmic bytes written per iso_start                 */
+    uint64_t delivered_bytes;    /* p*s*m                                                   */
+    uint64_t workspace_bytes;    /* workspace the request uses                              */
+} iso_request_info_t;
+
+/* ---- neighbourhood set-up (Section 2, set-up listing) ----------------------
+ * dims:       host, d ints, every p_j >= 1, 1 <= d <= ISO_MAX_DIMS, prod < 2^31.
+ * rel_coords: host, s*d ints, neighbour-major: C^0_0..C^0_{d-1}, C^1_0, ...
+ *             Arbitrary signed values, repeats and the zero vector are legal;
+ *             coordinates are reduced modulo p_j.  s >= 0.
+ * The arrays are copied; the order of the s vectors fixes the block order in
+ * the send and receive buffers.  Purely local host computation, O(s d). */
+int iso_neighborhood_create(int d, const int32_t *dims, int s,
+                            const int32_t *rel_coords, iso_comm_t *comm);
+int iso_neighborhood_info(iso_comm_t comm, iso_comm_info_t *info);
+/* Frees the handle and sets *comm = NULL.  Plans and requests made from it
+ * keep their own copy of what they need and stay valid. */
+int iso_neighborhood_free(iso_comm_t *comm);
+
+/* ---- schedules, host only (Algorithm 1; Sections 3.2 and 5) ----------------
+ * A plan lists, per launch, the block-moves every rank performs.  No device is
+ * touched: these calls work without a GPU and exist so that a schedule can be
+ * inspected and checked. */
+int iso_plan_create(iso_comm_t comm, int op, int algorithm, iso_plan_t *plan);
+int iso_plan_info(iso_plan_t plan, iso_plan_info_t *info);
+int iso_plan_round(iso_plan_t plan, int round, iso_round_info_t *info);
+/* Copies min(capacity, n_entries) entries of `round` to host array `out`. */
+int iso_plan_entries(iso_plan_t plan, int round, iso_plan_entry_t *out, int capacity);
+int iso_plan_free(iso_plan_t *plan);
+
+/* Bytes of device workspace an init call with these arguments needs (may be 0).
+ * All-to-all: the intermediate buffer of Algorithm 1, restricted to the blocks
+ * that make two or more hops.  Allgather: trie nodes that are not themselves
+ * neighbours.  The s-exchange algorithms need none. */
+int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t *bytes);
+
+/* ---- persistent collectives (Section 2, init/start listing) ----------------
+ * sendbuf:   device, read-only.  All-to-all: p*s blocks, [p][s][m], block (R,i)
+ *            is what rank R sends to rank R (+) C^i.  Allgather: [p][m].
+ * recvbuf:   device, [p][s][m]; after completion block (R,i) holds what rank
+ *            R (-) C^i sent (all-to-all: its i-th block; allgather: its block).
+ * m:         block size in bytes, any value >= 0 (m == 0 or s == 0: no-op).
+ *            Loads and stores are 16 bytes wide when m and the three base
+ *            addresses are multiples of 16, else the widest power of two that
+ *            divides them all.
+ * workspace: device, at least iso_workspace_bytes() bytes (NULL allowed when
+ *            that is 0).  Contents are scratch while a collective runs.
+ * The three ranges must not overlap (ISO_ERR_OVERLAP); in-place operation is
+ * not supported.  Each must lie inside one device allocation (ISO_ERR_POINTER).
+ * ISO_ERR_TOO_LARGE if p*m >= 2^36 (one block plane would exceed what a launch
+ * indexes).  The buffers are bound to the request; iso_start may be called any
+ * number of times.  Needs a GPU (uploads the index maps: one hipMalloc + one
+ * synchronous hipMemcpy). */
+int iso_neighbor_alltoall_init(const void *sendbuf, void *recvbuf, size_t m,
+                               void *workspace, size_t workspace_bytes,
+                               iso_comm_t comm, int algorithm, iso_request_t *req);
+int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m,
+                                void *workspace, size_t workspace_bytes,
+                                iso_comm_t comm, int algorithm, iso_request_t *req);
+
+/* Enqueues the launches of one collective on `hip_stream` (a hipStream_t; NULL
+ * = the default stream) and returns without waiting.  Rounds are ordered by the
+ * stream.  Calls on one request must not overlap in time on the device. */
+int iso_start(iso_request_t req, void *hip_stream);
+/* Enqueues only launches [first, first+count) of the request's launch list, in
+ * order (0 <= first, first+count <= launches of iso_request_info).  For timing
+ * individual rounds; running all ranges in order equals one iso_start. */
+int iso_start_range(iso_request_t req, int first, int count, void *hip_stream);
+/* Blocks the host until the most recent iso_start of this request completed
+ * (Section 7's proposed completion call). */
+int iso_wait(iso_request_t req);
+int iso_request_info(iso_request_t req, iso_request_info_t *info);
+/* Returns the plan the request executes (owned by the request; do not free). */
+int iso_request_plan(iso_request_t req, iso_plan_t *plan);
+int iso_request_free(iso_request_t *req);
+
+/* ---- diagnostics ----------------------------------------------------------- */
+const char *iso_error_string(int status);
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int iso_last_hip_error(void);
+/* Plain device-to-device copy of `bytes` bytes with the library's streaming
+ * kernel (16-byte accesses when alignment allows): the bandwidth ceiling that
+ * the round kernels are measured against.  src/dst: device, non-overlapping. */
+int iso_copy_reference(const void *src, void *dst, size_t bytes, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ISO_H */

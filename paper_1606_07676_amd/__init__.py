@@ -1,0 +1,21 @@
+"""MI355X-native isomorphic sparse all-to-all / allgather on a virtual torus.
+
+Thin Python binding over the C ABI of libiso.so (include/iso.h).  Every step of
+the collectives runs in the library's HIP kernels; this package only marshals
+arguments.  PyTorch is used by callers for device memory and streams.
+"""
+from .binding import (  # noqa: F401
+    IsoError, load_library, library_path,
+    ISO_OP_ALLTOALL, ISO_OP_ALLGATHER,
+    ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED,
+    ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK,
+    ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR,
+    ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP,
+    ISO_ERR_NOMEM, ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_MAX_DIMS,
+    Comm, Plan, Request,
+    iso_neighborhood_create, iso_neighborhood_info, iso_neighborhood_free,
+    iso_plan_create, iso_plan_info, iso_plan_round, iso_plan_entries, iso_plan_free,
+    iso_workspace_bytes, iso_neighbor_alltoall_init, iso_neighbor_allgather_init,
+    iso_start, iso_start_range, iso_wait, iso_request_info, iso_request_plan, iso_request_free,
+    iso_error_string, iso_last_hip_error, iso_copy_reference,
+)

@@ -1,0 +1,374 @@
+// Schedule builder for isomorphic sparse collectives (host only).
+//
+// All-to-all: Algorithm 1's alternating-buffer rule applied to the torus-direct
+// schedule of Section 5 (a block makes one hop per non-zero coordinate, and each
+// dimension has one round per distinct non-zero coordinate value).
+// Allgather: the prefix trie of Section 3.2, routed the same torus-direct way.
+// S-exchange: the straightforward algorithm of Section 3's first listing.
+#include "iso_plan.hpp"
+
+#include <algorithm>
+#include <functional>
+#include <numeric>
+#include <queue>
+
+namespace iso {
+
+int Comm::nnz(int i) const {
+    int n = 0;
+    for (int j = 0; j < d; ++j) n += c(i, j) != 0;
+    return n;
+}
+
+int Comm::rounds() const {
+    size_t n = 0;
+    for (const auto &v : values) n += v.size();
+    return (int)n;
+}
+
+int64_t Plan::entries() const {
+    int64_t n = 0;
+    for (const auto &r : rounds) n += (int64_t)r.entries.size();
+    return n;
+}
+
+int build_comm(int d, const int32_t *dims, int s, const int32_t *rel, Comm &out) {
+    if (d < 1 || d > ISO_MAX_DIMS || !dims || s < 0 || (s > 0 && !rel)) return ISO_ERR_ARG;
+    Comm c;
+    c.d = d;
+    c.s = s;
+    c.dims.assign(dims, dims + d);
+    c.p = 1;
+    for (int j = 0; j < d; ++j) {
+        if (dims[j] < 1) return ISO_ERR_ARG;
+        c.p *= dims[j];
+        if (c.p >= (int64_t(1) << 31)) return ISO_ERR_TOO_LARGE;
+    }
+    c.inner.assign(d, 1);
+    for (int j = d - 2; j >= 0; --j) c.inner[j] = c.inner[j + 1] * dims[j + 1];
+    c.raw.assign(rel, rel + (size_t)s * d);
+    c.can.resize((size_t)s * d);
+    c.values.assign(d, {});
+    for (int i = 0; i < s; ++i)
+        for (int j = 0; j < d; ++j) {
+            int64_t r = (int64_t)rel[(size_t)i * d + j] % dims[j];
+            if (r < 0) r += dims[j];
+            c.can[(size_t)i * d + j] = (int32_t)r;
+            if (r) c.values[j].push_back((int32_t)r);
+        }
+    for (auto &v : c.values) {
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());
+    }
+    out = std::move(c);
+    return ISO_SUCCESS;
+}
+
+static iso_plan_entry_t mk(int sb, int ss, int db, int ds, int shift, int nb) {
+    iso_plan_entry_t e;
+    e.src_buf = sb; e.src_slot = ss; e.dst_buf = db; e.dst_slot = ds;
+    e.shift = shift; e.neighbor = nb;
+    return e;
+}
+
+// ---------------------------------------------------------------------------
+// all-to-all, message-combining
+// ---------------------------------------------------------------------------
+static void plan_alltoall_combined(const Comm &c, bool by_dim, Plan &pl) {
+    const int s = c.s, d = c.d;
+    std::vector<int> hops(s), where(s, ISO_BUF_SEND), wslot(s, -1);
+    int nwork = 0;
+    Round self;
+    self.kind = ISO_ROUND_SELF;
+    for (int i = 0; i < s; ++i) {
+        hops[i] = c.nnz(i);
+        if (hops[i] >= 2) wslot[i] = nwork++;           // only these ever sit in the intermediate buffer
+        if (hops[i] == 0) self.entries.push_back(mk(ISO_BUF_SEND, i, ISO_BUF_RECV, i, 0, i));
+    }
+    pl.work_slots = nwork;
+    if (!self.entries.empty()) pl.rounds.push_back(std::move(self));
+    auto slot_in = [&](int buf, int i) { return buf == ISO_BUF_WORK ? wslot[i] : i; };
+    for (int j = 0; j < d; ++j) {
+        Round dim_round;
+        dim_round.dim = j;
+        for (int32_t v : c.values[j]) {
+            Round r;
+            r.dim = j;
+            for (int i = 0; i < s; ++i) {
+                if (c.c(i, j) != v) continue;
+                // received into the receive buffer when an odd number of hops remains,
+                // so that the last hop (one remaining) always lands there
+                const int dst = (hops[i] % 2 == 0) ? ISO_BUF_WORK : ISO_BUF_RECV;
+                const int src = where[i];
+                r.entries.push_back(mk(src, slot_in(src, i), dst, slot_in(dst, i), v, i));
+                where[i] = dst;
+                --hops[i];
+            }
+            if (by_dim)
+                dim_round.entries.insert(dim_round.entries.end(), r.entries.begin(), r.entries.end());
+            else
+                pl.rounds.push_back(std::move(r));
+        }
+        if (by_dim && !dim_round.entries.empty()) {
+            std::stable_sort(dim_round.entries.begin(), dim_round.entries.end(),
+                             [](const iso_plan_entry_t &a, const iso_plan_entry_t &b) {
+                                 return a.neighbor < b.neighbor;
+                             });
+            pl.rounds.push_back(std::move(dim_round));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// allgather, message-combining along the prefix trie
+// ---------------------------------------------------------------------------
+namespace {
+struct Node {
+    int parent;        // node index, -1 for the root
+    int level;         // index into the dimension order; root: -1
+    int32_t value;     // residue on the edge from the parent
+    int first, last;   // range [first, last) of the sorted neighbour list below this node
+    int store;         // nearest node on the path to the root (incl. self) that holds a copy
+    int buf, slot;     // where that copy sits (stored nodes only; root: send block)
+    int last_read;     // last level at which a child reads this copy
+    std::vector<int> terminals;  // neighbours equal to this prefix padded with zeros
+};
+}  // namespace
+
+static void build_trie(const Comm &c, const std::vector<int32_t> &order,
+                       std::vector<int> &sorted, std::vector<Node> &nodes) {
+    const int s = c.s, d = c.d;
+    sorted.resize(s);
+    std::iota(sorted.begin(), sorted.end(), 0);
+    std::stable_sort(sorted.begin(), sorted.end(), [&](int a, int b) {
+        for (int t = 0; t < d; ++t) {
+            int32_t x = c.c(a, order[t]), y = c.c(b, order[t]);
+            if (x != y) return x < y;
+        }
+        return false;
+    });
+    nodes.clear();
+    Node root{};
+    root.parent = -1; root.level = -1; root.value = 0; root.first = 0; root.last = s;
+    root.store = 0; root.buf = ISO_BUF_SEND; root.slot = 0; root.last_read = -1;
+    nodes.push_back(root);
+    size_t level_begin = 0, level_end = 1;
+    for (int t = 0; t < d; ++t) {
+        const int j = order[t];
+        for (size_t n = level_begin; n < level_end; ++n) {
+            int a = nodes[n].first;
+            const int end = nodes[n].last;
+            while (a < end) {
+                const int32_t v = c.c(sorted[a], j);
+                int b = a;
+                while (b < end && c.c(sorted[b], j) == v) ++b;
+                Node ch{};
+                ch.parent = (int)n; ch.level = t; ch.value = v; ch.first = a; ch.last = b;
+                ch.buf = -1; ch.slot = -1; ch.last_read = -1;
+                ch.store = v ? (int)nodes.size() : nodes[n].store;
+                if (v) {
+                    // neighbours that end here: all later coordinates zero; zero sorts first
+                    for (int q = a; q < b; ++q) {
+                        bool rest_zero = true;
+                        for (int u = t + 1; u < d && rest_zero; ++u)
+                            rest_zero = c.c(sorted[q], order[u]) == 0;
+                        if (!rest_zero) break;
+                        ch.terminals.push_back(sorted[q]);
+                    }
+                }
+                nodes.push_back(std::move(ch));
+                a = b;
+            }
+        }
+        level_begin = level_end;
+        level_end = nodes.size();
+    }
+}
+
+static int64_t trie_moves(const std::vector<Node> &nodes) {
+    int64_t n = 0;
+    for (const Node &nd : nodes)
+        if (nd.level >= 0 && nd.value) n += nd.terminals.empty() ? 1 : (int64_t)nd.terminals.size();
+    return n;
+}
+
+std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
+    const int d = c.d;
+    std::vector<int32_t> ident(d), heur(d);
+    std::iota(ident.begin(), ident.end(), 0);
+    heur = ident;
+    // candidate: dimensions with few distinct values first, so that prefixes are
+    // shared by many neighbours (Section 3.2's remark on visiting order)
+    std::vector<int> distinct(d), maxmult(d, 0);
+    for (int j = 0; j < d; ++j) {
+        std::vector<int32_t> col(c.s);
+        for (int i = 0; i < c.s; ++i) col[i] = c.c(i, j);
+        std::sort(col.begin(), col.end());
+        int run = 0;
+        distinct[j] = 0;
+        for (int i = 0; i < c.s; ++i) {
+            if (i == 0 || col[i] != col[i - 1]) { ++distinct[j]; run = 0; }
+            maxmult[j] = std::max(maxmult[j], ++run);
+        }
+    }
+    std::stable_sort(heur.begin(), heur.end(), [&](int a, int b) {
+        if (distinct[a] != distinct[b]) return distinct[a] < distinct[b];
+        return maxmult[a] > maxmult[b];
+    });
+    std::vector<int> sorted;
+    std::vector<Node> nodes;
+    build_trie(c, ident, sorted, nodes);
+    const int64_t mi = trie_moves(nodes);
+    int64_t mh = mi;
+    if (heur != ident) {
+        build_trie(c, heur, sorted, nodes);
+        mh = trie_moves(nodes);
+    }
+    if (mh < mi) {
+        if (moves_out) *moves_out = mh;
+        return heur;
+    }
+    if (moves_out) *moves_out = mi;
+    return ident;
+}
+
+static void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
+    const int s = c.s, d = c.d;
+    pl.dim_order = allgather_dim_order(c, nullptr);
+    std::vector<int> sorted;
+    std::vector<Node> nodes;
+    build_trie(c, pl.dim_order, sorted, nodes);
+
+    Round self;
+    self.kind = ISO_ROUND_SELF;
+    for (int i = 0; i < s; ++i)
+        if (c.nnz(i) == 0) self.entries.push_back(mk(ISO_BUF_SEND, 0, ISO_BUF_RECV, i, 0, i));
+    if (!self.entries.empty()) pl.rounds.push_back(std::move(self));
+
+    // which copies are read at which level
+    for (size_t n = 1; n < nodes.size(); ++n)
+        if (nodes[n].value) {
+            Node &src = nodes[nodes[nodes[n].parent].store];
+            src.last_read = std::max(src.last_read, nodes[n].level);
+        }
+    // storage: receive slot when the prefix is itself a neighbour, else a workspace
+    // slot that is reused once every reader's level has passed
+    std::priority_queue<int, std::vector<int>, std::greater<int>> free_slots;
+    std::vector<std::pair<int, int>> live;   // (last_read level, slot)
+    int nwork = 0;
+    size_t n = 1;
+    for (int t = 0; t < d; ++t) {
+        for (size_t q = 0; q < live.size();) {
+            if (live[q].first < t) {
+                free_slots.push(live[q].second);
+                live[q] = live.back();
+                live.pop_back();
+            } else {
+                ++q;
+            }
+        }
+        for (; n < nodes.size() && nodes[n].level == t; ++n) {
+            Node &nd = nodes[n];
+            if (!nd.value) continue;
+            if (!nd.terminals.empty()) {
+                nd.buf = ISO_BUF_RECV;
+                nd.slot = nd.terminals[0];
+            } else {
+                nd.buf = ISO_BUF_WORK;
+                if (free_slots.empty()) {
+                    nd.slot = nwork++;
+                } else {
+                    nd.slot = free_slots.top();
+                    free_slots.pop();
+                }
+                live.emplace_back(nd.last_read, nd.slot);
+            }
+        }
+    }
+    pl.work_slots = nwork;
+
+    auto by_dst = [](const iso_plan_entry_t &a, const iso_plan_entry_t &b) {
+        return a.dst_buf != b.dst_buf ? a.dst_buf < b.dst_buf : a.dst_slot < b.dst_slot;
+    };
+    n = 1;
+    for (int t = 0; t < d; ++t) {
+        const int j = pl.dim_order[t];
+        const size_t lvl_begin = n;
+        while (n < nodes.size() && nodes[n].level == t) ++n;
+        Round dim_round;
+        dim_round.dim = j;
+        for (int32_t v : c.values[j]) {
+            Round r;
+            r.dim = j;
+            for (size_t q = lvl_begin; q < n; ++q) {
+                const Node &nd = nodes[q];
+                if (nd.value != v) continue;
+                const Node &src = nodes[nodes[nd.parent].store];
+                if (nd.terminals.empty()) {
+                    r.entries.push_back(mk(src.buf, src.slot, nd.buf, nd.slot, v, -1));
+                } else {
+                    for (int i : nd.terminals)       // repeated offsets: one copy each
+                        r.entries.push_back(mk(src.buf, src.slot, ISO_BUF_RECV, i, v, i));
+                }
+            }
+            std::stable_sort(r.entries.begin(), r.entries.end(), by_dst);
+            if (by_dim)
+                dim_round.entries.insert(dim_round.entries.end(), r.entries.begin(), r.entries.end());
+            else if (!r.entries.empty())
+                pl.rounds.push_back(std::move(r));
+        }
+        if (by_dim && !dim_round.entries.empty()) {
+            std::stable_sort(dim_round.entries.begin(), dim_round.entries.end(), by_dst);
+            pl.rounds.push_back(std::move(dim_round));
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// straightforward s-exchange
+// ---------------------------------------------------------------------------
+static void plan_s_exchange(const Comm &c, int op, bool fused, Plan &pl) {
+    Round all;
+    all.kind = ISO_ROUND_VECTOR;
+    for (int i = 0; i < c.s; ++i) {
+        iso_plan_entry_t e = mk(ISO_BUF_SEND, op == ISO_OP_ALLTOALL ? i : 0, ISO_BUF_RECV, i, 0, i);
+        if (fused) {
+            all.entries.push_back(e);
+        } else {
+            Round r;
+            r.kind = ISO_ROUND_VECTOR;
+            r.entries.push_back(e);
+            pl.rounds.push_back(std::move(r));
+        }
+    }
+    if (fused && !all.entries.empty()) pl.rounds.push_back(std::move(all));
+}
+
+int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
+    if (op != ISO_OP_ALLTOALL && op != ISO_OP_ALLGATHER) return ISO_ERR_ARG;
+    Plan pl;
+    pl.op = op;
+    pl.algorithm = algorithm;
+    pl.comm = c;
+    pl.dim_order.resize(c.d);
+    std::iota(pl.dim_order.begin(), pl.dim_order.end(), 0);
+    switch (algorithm) {
+        case ISO_ALG_COMBINED:
+        case ISO_ALG_COMBINED_BYDIM:
+            if (op == ISO_OP_ALLTOALL)
+                plan_alltoall_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
+            else
+                plan_allgather_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
+            break;
+        case ISO_ALG_SX_ROUNDS:
+        case ISO_ALG_SX_FUSED:
+            plan_s_exchange(c, op, algorithm == ISO_ALG_SX_FUSED, pl);
+            break;
+        default:
+            return ISO_ERR_ARG;
+    }
+    out = std::move(pl);
+    return ISO_SUCCESS;
+}
+
+}  // namespace iso

@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+bit for bit, on seeded inputs.  Small cases compare every byte with the numpy
+oracle; the five named workloads run at full size in the launch configuration
+the benchmark times and are compared in rank chunks with what the oracle says
+each received block must be (the block generated for the oracle's source rank).
+"""
+import numpy as np
+import pytest
+import torch
+
+import iso_inputs as gen
+import paper_1606_07676_amd as iso
+from oracle import iso_oracle as orc
+from oracle import c_twin
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused"}
+
+SMALL = [
+    ((5,), [(1,), (-2,), (7,)]),
+    ((4, 3), [(1, 0), (0, -1), (1, 1), (-1, 2), (0, 0), (1, 1)]),
+    ((3, 2, 4), gen.moore(3, 1)),
+    ((2, 1, 5), [(1, 0, 2), (0, 3, -1), (-5, 0, 6), (0, 0, 0), (2, 7, 5)]),
+    ((2, 2, 2, 2), gen.moore(4, 1)),                      # s = 80 > p = 16
+    ((6, 5), gen.von_neumann(2, 2)),
+    ((9, 9, 9), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0), (3, 3, 2),
+                 (4, 0, 1), (4, 0, 2), (4, 1, 1)]),
+    ((4, 4, 4, 4, 4), gen.random_distinct(5, -3, 3, 40, 99)),
+    ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),
+    ((37, 11), gen.moore(2, 2)),                          # several tiles, ragged tail
+    ((1, 1), [(0, 0), (3, -2)]),                          # a single process
+]
+BLOCK_SIZES = [16, 48, 256, 1, 6, 20, 8, 1040]
+
+
+def _comm(dims, offsets):
+    return iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(len(offsets), len(dims)))
+
+
+def _run(dims, offsets, op, alg, m, send, misalign=0, stream=None, starts=1):
+    """send: device uint8 tensor.  Returns recv (p, s, m) device tensor."""
+    p, s = int(np.prod(dims)), len(offsets)
+    comm = _comm(dims, offsets)
+    wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+    recv_store = torch.full((p * s * m + misalign + 16,), 0xEE, dtype=torch.uint8, device=DEV)
+    recv = recv_store[misalign:misalign + p * s * m]
+    work = torch.full((wsb + 16,), 0xDD, dtype=torch.uint8, device=DEV)[:wsb] if wsb else None
+    init = iso.iso_neighbor_alltoall_init if op == iso.ISO_OP_ALLTOALL else iso.iso_neighbor_allgather_init
+    req = init(send, recv, m, work, comm, alg)
+    info = iso.iso_request_info(req)
+    for _ in range(starts):
+        iso.iso_start(req, stream)
+    iso.iso_wait(req)
+    iso.iso_request_free(req)
+    return recv.view(p, s, m), info
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_alltoall_every_byte(case, alg):
+    dims, offsets = SMALL[case]
+    p, s = int(np.prod(dims)), len(offsets)
+    for m in BLOCK_SIZES:
+        send_h = gen.alltoall_send(100 + case, p, s, m)
+        send = torch.from_numpy(send_h).to(DEV)
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, alg, m, send)
+        want = orc.alltoall(dims, offsets, send_h)
+        assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} m={m} alg={alg}"
+        assert np.array_equal(send.cpu().numpy(), send_h), "send buffer was modified"
+        assert info["delivered_bytes"] == p * s * m
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("case", range(len(SMALL)))
+def test_small_allgather_every_byte(case, alg):
+    dims, offsets = SMALL[case]
+    p = int(np.prod(dims))
+    for m in BLOCK_SIZES:
+        send_h = gen.allgather_send(200 + case, p, m)
+        send = torch.from_numpy(send_h).to(DEV)
+        recv, _ = _run(dims, offsets, iso.ISO_OP_ALLGATHER, alg, m, send)
+        want = orc.allgather(dims, offsets, send_h)
+        assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} m={m} alg={alg}"
+
+
+@pytest.mark.parametrize("misalign,vec", [(0, 16), (8, 8), (4, 4), (2, 2), (1, 1)])
+def test_vector_width_follows_alignment(misalign, vec):
+    dims, offsets = (6, 5), gen.moore(2, 1)
+    p, s, m = 30, 8, 64
+    send_h = gen.alltoall_send(5, p, s, m)
+    send = torch.from_numpy(send_h).to(DEV)
+    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m, send, misalign=misalign)
+    assert info["vector_bytes"] == vec
+    assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h))
+
+
+def test_restart_and_side_stream_give_the_same_result():
+    cfg = gen.get_config(1)
+    send_h = gen.alltoall_send(3, cfg.p, cfg.s, cfg.m)
+    send = torch.from_numpy(send_h).to(DEV)
+    want = orc.alltoall(cfg.dims, cfg.offsets, send_h)
+    side = torch.cuda.Stream()
+    for alg in ALGS:
+        recv, info = _run(cfg.dims, cfg.offsets, iso.ISO_OP_ALLTOALL, alg, cfg.m, send, stream=side, starts=3)
+        assert np.array_equal(recv.cpu().numpy(), want)
+    assert info["launches"] == 1
+
+
+def test_noop_and_error_paths():
+    comm = _comm((4, 4), gen.moore(2, 1))
+    p, s, m = 16, 8, 32
+    send = torch.zeros(p * s * m, dtype=torch.uint8, device=DEV)
+    recv = torch.zeros(p * s * m, dtype=torch.uint8, device=DEV)
+    work = torch.zeros(p * s * m, dtype=torch.uint8, device=DEV)
+    # m == 0: success, no launches
+    req = iso.iso_neighbor_alltoall_init(send, recv, 0, None, comm)
+    assert iso.iso_request_info(req)["launches"] == 0
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    # s == 0
+    empty = iso.iso_neighborhood_create((4, 4), np.zeros((0, 2), np.int32))
+    req = iso.iso_neighbor_allgather_init(None, None, 64, None, empty)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    # overlap
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(send, send[16:], m, work, comm, workspace_bytes=work.numel())
+    assert e.value.status in (iso.ISO_ERR_OVERLAP, iso.ISO_ERR_POINTER)
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(send, send, m, work, comm)
+    assert e.value.status == iso.ISO_ERR_OVERLAP
+    # workspace too small / missing
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(send, recv, m, work[:64], comm)
+    assert e.value.status == iso.ISO_ERR_WORKSPACE
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(send, recv, m, None, comm)
+    assert e.value.status == iso.ISO_ERR_WORKSPACE
+    # a host pointer is refused before any kernel sees it
+    host = np.zeros(p * s * m, np.uint8)
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(host.ctypes.data, recv, m, work, comm)
+    assert e.value.status == iso.ISO_ERR_POINTER
+    # a device buffer whose allocation is too short for p*s*m (64 KiB blocks: 8 MiB needed,
+    # while a 64-byte tensor sits in a 2 MiB allocator segment)
+    big_m = 65536
+    big_send = torch.zeros(p * s * big_m, dtype=torch.uint8, device=DEV)
+    small = torch.zeros(64, dtype=torch.uint8, device=DEV)
+    fused = iso.ISO_ALG_SX_FUSED
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(big_send, small.data_ptr(), big_m, None, comm, fused)
+    assert e.value.status == iso.ISO_ERR_POINTER
+
+
+def test_copy_reference_copies():
+    n = (1 << 22) + 48
+    src = torch.randint(0, 256, (n,), dtype=torch.uint8, device=DEV)
+    dst = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    iso.iso_copy_reference(src, dst, n)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+    dst.zero_()
+    iso.iso_copy_reference(src[1:], dst[1:], n - 1)       # unaligned: narrow path
+    torch.cuda.synchronize()
+    assert torch.equal(src[1:], dst[1:]) and int(dst[0]) == 0
+
+
+# ---------------------------------------------------------------- named workloads, full size
+
+def _check_full(cfg, op, alg, m, seed, host_oracle):
+    """Run one collective at full size and compare all of recv, in rank chunks,
+    with the block the generator gives for the oracle's source rank."""
+    p, s = cfg.p, cfg.s
+    if op == iso.ISO_OP_ALLTOALL:
+        send = gen.alltoall_send_torch(seed, p, s, m, cfg.kind, device=DEV)
+    else:
+        send = gen.allgather_send_torch(seed, p, m, cfg.kind, device=DEV)
+    keep = send.clone() if send.numel() <= (1 << 30) else None
+    recv, info = _run(cfg.dims, cfg.offsets, op, alg, m, send)
+    assert info["vector_bytes"] == 16
+    src = orc.source_ranks(cfg.dims, cfg.offsets)                 # (p, s) from the oracle
+    slots = torch.arange(s, device=DEV)[None, :]
+    chunk = max(1, (256 << 20) // (s * m))
+    for lo in range(0, p, chunk):
+        hi = min(p, lo + chunk)
+        sr = torch.from_numpy(src[lo:hi]).to(DEV)
+        if op == iso.ISO_OP_ALLTOALL:
+            want = gen.block_bytes_torch(seed, sr, slots, m, cfg.kind)
+        else:
+            want = gen.block_bytes_torch(seed ^ gen.ALLGATHER_TWEAK, sr, torch.zeros_like(sr), m, cfg.kind)
+        assert torch.equal(recv[lo:hi], want), f"{cfg.name} op={op} alg={alg} ranks {lo}:{hi}"
+    if keep is not None:
+        assert torch.equal(send, keep), "send buffer was modified"
+    if host_oracle:
+        # the same comparison against the oracle run on the host buffer, every byte
+        send_h = send.cpu().numpy()
+        fn = c_twin.alltoall if op == iso.ISO_OP_ALLTOALL else c_twin.allgather
+        want_h, _ = fn(cfg.dims, cfg.offsets, send_h)
+        assert np.array_equal(recv.cpu().numpy(), want_h)
+    return info
+
+
+def _ops(cfg):
+    return [iso.ISO_OP_ALLTOALL if o == "alltoall" else iso.ISO_OP_ALLGATHER for o in cfg.ops]
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("key", [1, 2, 3, 4])
+def test_named_workloads_full_size(key, alg):
+    cfg = gen.get_config(key)
+    for op in _ops(cfg):
+        for m in (cfg.m_sweep or (cfg.m,)):
+            info = _check_full(cfg, op, alg, m, seed=key * 1000 + m,
+                               host_oracle=(alg == iso.ISO_ALG_COMBINED and m == cfg.m))
+            if alg == iso.ISO_ALG_COMBINED:
+                want_rounds = len(orc.direct_rounds(cfg.dims, cfg.offsets))
+                assert info["launches"] == want_rounds
+                moves = (orc.direct_alltoall_volume(cfg.dims, cfg.offsets) if op == iso.ISO_OP_ALLTOALL
+                         else orc.direct_allgather_volume(cfg.dims, cfg.offsets))
+                assert info["bytes_read"] == moves * cfg.p * m == info["bytes_written"]
+    # a second seed on the combined path
+    if alg == iso.ISO_ALG_COMBINED:
+        _check_full(cfg, _ops(cfg)[0], alg, cfg.m, seed=77 + key, host_oracle=False)
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+def test_config5_full_size(alg):
+    cfg = gen.get_config(5)
+    for op in _ops(cfg):
+        info = _check_full(cfg, op, alg, cfg.m, seed=5005, host_oracle=False)
+        torch.cuda.empty_cache()
+    assert info["delivered_bytes"] == cfg.p * cfg.s * cfg.m

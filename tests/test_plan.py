@@ -1,0 +1,287 @@
+"""Host logic of libiso through the C ABI, no GPU: symbol export, argument
+checks, and the schedules (round lists and block index maps) checked against
+the oracle's counts and, by replaying the index maps with numpy.roll on host
+arrays, against the oracle's results."""
+import os
+import re
+import subprocess
+import tempfile
+
+import numpy as np
+import pytest
+
+import iso_inputs as gen
+import paper_1606_07676_amd as iso
+from oracle import iso_oracle as orc
+from conftest import ROOT
+
+RNG = np.random.default_rng(7)
+
+CASES = [
+    ((5,), [(1,), (-2,), (7,)]),
+    ((4, 3), [(1, 0), (0, -1), (1, 1), (-1, 2), (0, 0), (1, 1)]),
+    ((3, 2, 4), gen.moore(3, 1)),
+    ((2, 1, 5), [(1, 0, 2), (0, 3, -1), (-5, 0, 6), (0, 0, 0), (2, 7, 5)]),
+    ((2, 2, 2, 2), gen.moore(4, 1)),
+    ((6, 5), gen.von_neumann(2, 2)),
+    ((7, 3, 2), gen.positive_octant(3, 3)),
+    ((9, 9, 9), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0), (3, 3, 2),
+                 (4, 0, 1), (4, 0, 2), (4, 1, 1)]),
+    ((4, 4, 4, 4, 4), gen.random_distinct(5, -3, 3, 40, 99)),
+    ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),     # repeats
+    ((3, 3), []),                                                         # empty neighbourhood
+]
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "iso.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(iso_[a-z_0-9]+)\s*\(", header))
+    assert len(declared) >= 19
+    lib = iso.load_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"{name} declared in iso.h but not exported"
+    out = subprocess.check_output(["nm", "-D", "--defined-only", iso.library_path()], text=True)
+    exported = set(re.findall(r" T (iso_[a-z_0-9]+)", out))
+    assert declared == exported
+
+
+def test_error_strings_and_bad_arguments():
+    assert iso.iso_error_string(0) == "success"
+    for code in range(1, 8):
+        assert iso.iso_error_string(code) not in ("success", "unknown status")
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighborhood_create([4, 0], [(1, 1)])
+    assert e.value.status == iso.ISO_ERR_ARG
+    with pytest.raises(iso.IsoError):
+        iso.iso_neighborhood_create([2] * 17, [[1] * 17])
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighborhood_create([65536, 65536], [(1, 1)])
+    assert e.value.status == iso.ISO_ERR_TOO_LARGE
+    comm = iso.iso_neighborhood_create([4, 4], [(1, 1)])
+    with pytest.raises(iso.IsoError):
+        iso.iso_plan_create(comm, 5, iso.ISO_ALG_COMBINED)
+    with pytest.raises(iso.IsoError):
+        iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL, 17)
+    plan = iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL)
+    with pytest.raises(iso.IsoError):
+        iso.iso_plan_round(plan, 99)
+    lib = iso.load_library()
+    assert lib.iso_neighborhood_create(2, None, 0, None, None) == iso.ISO_ERR_ARG
+    assert lib.iso_start(None, None) == iso.ISO_ERR_ARG
+    assert lib.iso_wait(None) == iso.ISO_ERR_ARG
+    assert lib.iso_request_free(None) == iso.ISO_ERR_ARG
+    # init with a null communicator never reaches the device
+    import ctypes
+    h = ctypes.c_void_p(123)
+    assert lib.iso_neighbor_alltoall_init(None, None, 16, None, 0, None, 0, ctypes.byref(h)) == iso.ISO_ERR_ARG
+    assert h.value is None
+
+
+def _plan_rounds(plan):
+    n = iso.iso_plan_info(plan)["launches"]
+    return [(iso.iso_plan_round(plan, r), iso.iso_plan_entries(plan, r)) for r in range(n)]
+
+
+@pytest.mark.parametrize("dims,offsets", CASES)
+def test_comm_info_matches_oracle_counts(dims, offsets):
+    comm = iso.iso_neighborhood_create(dims, offsets) if offsets else \
+        iso.iso_neighborhood_create(dims, np.zeros((0, len(dims)), np.int32))
+    info = iso.iso_neighborhood_info(comm)
+    assert info["p"] == int(np.prod(dims)) and info["s"] == len(offsets) and info["d"] == len(dims)
+    assert info["rounds"] == len(orc.direct_rounds(dims, offsets))
+    assert info["alltoall_moves"] == orc.direct_alltoall_volume(dims, offsets)
+    can = orc.canonical(dims, offsets)
+    assert info["self_slots"] == sum(1 for C in can if not any(C))
+    # allgather: never more than the identity-order trie, plus one extra copy per repeated offset
+    dup_extra = sum(can[:i].count(C) > 0 and any(C) for i, C in enumerate(can))
+    assert info["allgather_moves"] <= orc.direct_allgather_volume(dims, offsets) + dup_extra
+    assert info["allgather_moves"] <= info["alltoall_moves"]
+
+
+def _replay(dims, offsets, op, rounds, work_slots, send, m):
+    """Apply the plan's index maps to host arrays.  A SHIFT entry is a
+    numpy.roll of one slot plane along one axis; all reads of a launch happen
+    before its writes (one kernel launch has no internal ordering)."""
+    d, s = len(dims), len(offsets)
+    p = int(np.prod(dims))
+    shape = tuple(dims)
+    bufs = {
+        iso.ISO_BUF_SEND: send.reshape(shape + ((s, m) if op == iso.ISO_OP_ALLTOALL else (1, m))),
+        iso.ISO_BUF_RECV: np.full(shape + (max(s, 1), m), 0xEE, np.uint8),
+        iso.ISO_BUF_WORK: np.full(shape + (max(work_slots, 1), m), 0xDD, np.uint8),
+    }
+    written = set()
+    for info, entries in rounds:
+        reads, writes, staged = set(), set(), []
+        for e in entries:
+            src = bufs[e["src_buf"]][..., e["src_slot"], :]
+            if info["kind"] == iso.ISO_ROUND_SHIFT:
+                assert 0 < e["shift"] < dims[info["dim"]]
+                data = np.roll(src, e["shift"], axis=info["dim"])
+            elif info["kind"] == iso.ISO_ROUND_SELF:
+                data = src.copy()
+            else:
+                data = np.roll(src, tuple(offsets[e["neighbor"]]), axis=tuple(range(d)))
+            staged.append((e, data))
+            reads.add((e["src_buf"], e["src_slot"]))
+            assert (e["dst_buf"], e["dst_slot"]) not in writes, "two entries write one block"
+            writes.add((e["dst_buf"], e["dst_slot"]))
+            assert e["dst_buf"] != iso.ISO_BUF_SEND, "send buffer must never be written"
+            if e["src_buf"] != iso.ISO_BUF_SEND:
+                assert (e["src_buf"], e["src_slot"]) in written, "reads a block nobody wrote"
+            if e["dst_buf"] == iso.ISO_BUF_WORK:
+                assert 0 <= e["dst_slot"] < work_slots
+        assert not (reads & writes), "a block is read and written in one launch"
+        for e, data in staged:
+            bufs[e["dst_buf"]][..., e["dst_slot"], :] = data
+            written.add((e["dst_buf"], e["dst_slot"]))
+    return bufs[iso.ISO_BUF_RECV].reshape(p, max(s, 1), m)[:, :s], written
+
+
+@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("dims,offsets", CASES)
+def test_alltoall_plan_reaches_the_oracle_result(dims, offsets, alg):
+    p, s, m = int(np.prod(dims)), len(offsets), 3
+    comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, len(dims)))
+    plan = iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL, alg)
+    pinfo = iso.iso_plan_info(plan)
+    rounds = _plan_rounds(plan)
+    send = RNG.integers(0, 256, size=(p, s, m), dtype=np.uint8)
+    keep = send.copy()
+    recv, written = _replay(dims, offsets, iso.ISO_OP_ALLTOALL, rounds, pinfo["work_slots"], send, m)
+    assert np.array_equal(recv, orc.alltoall(dims, offsets, send))
+    assert np.array_equal(send, keep)
+    assert {(iso.ISO_BUF_RECV, i) for i in range(s)} <= written
+    can = orc.canonical(dims, offsets)
+    n_self = sum(1 for C in can if not any(C))
+    if alg in (iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM):
+        assert pinfo["entries"] == orc.direct_alltoall_volume(dims, offsets) + n_self
+        assert pinfo["work_slots"] == sum(1 for C in can if sum(1 for c in C if c) >= 2)
+        shift_rounds = [r for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT]
+        if alg == iso.ISO_ALG_COMBINED:
+            want = orc.direct_rounds(dims, offsets)
+            assert [(r[0]["dim"], r[1][0]["shift"]) for r in shift_rounds] == want
+            for info, entries in shift_rounds:
+                assert len({e["shift"] for e in entries}) == 1
+        else:
+            assert len(shift_rounds) == len({j for j, _ in orc.direct_rounds(dims, offsets)})
+        assert len(rounds) - len(shift_rounds) == (1 if n_self else 0)
+    else:
+        assert pinfo["entries"] == s and pinfo["work_slots"] == 0
+        assert len(rounds) == (s if alg == iso.ISO_ALG_SX_ROUNDS else min(s, 1))
+
+
+@pytest.mark.parametrize("alg", ALGS)
+@pytest.mark.parametrize("dims,offsets", CASES)
+def test_allgather_plan_reaches_the_oracle_result(dims, offsets, alg):
+    p, s, m = int(np.prod(dims)), len(offsets), 3
+    comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, len(dims)))
+    plan = iso.iso_plan_create(comm, iso.ISO_OP_ALLGATHER, alg)
+    pinfo = iso.iso_plan_info(plan)
+    rounds = _plan_rounds(plan)
+    send = RNG.integers(0, 256, size=(p, m), dtype=np.uint8)
+    recv, written = _replay(dims, offsets, iso.ISO_OP_ALLGATHER, rounds, pinfo["work_slots"], send, m)
+    assert np.array_equal(recv, orc.allgather(dims, offsets, send))
+    assert {(iso.ISO_BUF_RECV, i) for i in range(s)} <= written
+    if alg in (iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM):
+        order = pinfo["dim_order"][:len(dims)]
+        assert sorted(order) == list(range(len(dims)))
+        can = orc.canonical(dims, offsets)
+        n_self = sum(1 for C in can if not any(C))
+        dup_extra = sum(can[:i].count(C) > 0 and any(C) for i, C in enumerate(can))
+        assert pinfo["entries"] == orc.direct_allgather_volume(dims, offsets, order) + dup_extra + n_self
+        assert pinfo["entries"] - n_self == iso.iso_neighborhood_info(comm)["allgather_moves"]
+        if alg == iso.ISO_ALG_COMBINED:
+            n_shift = sum(1 for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT)
+            assert n_shift == len(orc.direct_rounds(dims, offsets))
+
+
+def test_figure1_example_plan(golden):
+    offs = [tuple(int(x) for x in t.split(",")) for t in golden["fig1_offsets"].split(";")]
+    comm = iso.iso_neighborhood_create((16, 16, 16), offs)
+    info = iso.iso_neighborhood_info(comm)
+    assert info["rounds"] == int(golden["fig1_direct_rounds"])
+    assert info["alltoall_moves"] == int(golden["fig1_direct_V"])
+    assert info["allgather_moves"] == int(golden["fig1_direct_W"])
+    assert info["self_slots"] == 1
+    ag = iso.iso_plan_create(comm, iso.ISO_OP_ALLGATHER)
+    pi = iso.iso_plan_info(ag)
+    assert pi["dim_order"][:3] == [0, 1, 2]
+    shift = [(i, e) for i, e in _plan_rounds(ag) if i["kind"] == iso.ISO_ROUND_SHIFT]
+    assert [i["n_entries"] for i, _ in shift] == [int(x) for x in golden["fig1_direct_allgather_k"].split(",")]
+    # four trie nodes are not neighbours themselves: (3), (4), (3,3), (4,1); those of the
+    # first level are still being read when the second level is written: four slots
+    temps = [e for _, es in shift for e in es if e["dst_buf"] == iso.ISO_BUF_WORK]
+    assert len(temps) == 4 and pi["work_slots"] == 4
+    a2a = iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL)
+    shift = [i for i, _ in _plan_rounds(a2a) if i["kind"] == iso.ISO_ROUND_SHIFT]
+    assert [i["n_entries"] for i in shift] == [int(x) for x in golden["fig1_direct_alltoall_k"].split(",")]
+
+
+def test_config_constants():
+    want = {  # name prefix -> (rounds, a2a moves, allgather moves, a2a k per round)
+        "c1": (4, 12, 8), "c2": (6, 54, 26), "c3": (8, 16, 12), "c4": (6, 54, 26),
+    }
+    for cfg in gen.CONFIGS:
+        comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
+        info = iso.iso_neighborhood_info(comm)
+        key = cfg.name[:2]
+        if key in want:
+            assert (info["rounds"], info["alltoall_moves"], info["allgather_moves"]) == want[key]
+        else:
+            assert info["rounds"] == len(orc.direct_rounds(cfg.dims, cfg.offsets)) <= 30
+            assert info["allgather_moves"] <= info["alltoall_moves"]
+    c2 = gen.get_config(2)
+    comm = iso.iso_neighborhood_create(c2.dims, c2.offsets)
+    a2a = [i["n_entries"] for i, _ in _plan_rounds(iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL))]
+    ag = [i["n_entries"] for i, _ in _plan_rounds(iso.iso_plan_create(comm, iso.ISO_OP_ALLGATHER))]
+    assert a2a == [9] * 6 and sorted(ag) == [1, 1, 3, 3, 9, 9]
+    assert iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED, 256) == 0
+    assert iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, 256) == 20 * 32768 * 256
+    assert iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_SX_FUSED, 256) == 0
+
+
+def test_allgather_workspace_slots_are_reused():
+    cfg = gen.get_config(5)
+    comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
+    plan = iso.iso_plan_create(comm, iso.ISO_OP_ALLGATHER)
+    pi = iso.iso_plan_info(plan)
+    temps = sum(1 for _, es in _plan_rounds(plan) for e in es if e["dst_buf"] == iso.ISO_BUF_WORK)
+    assert 0 < pi["work_slots"] < temps
+
+
+FASTDIV_TEST = r"""
+#include <cstdio>
+#include <cstdint>
+#include "iso_fastdiv.hpp"
+int main() {
+    const uint32_t divs[] = {1,2,3,5,7,8,9,16,26,27,31,32,33,63,64,255,256,257,1000,4095,4096,
+                             65535,65536,65537,262144,1000003,(1u<<30)-1,1u<<30,(1u<<31)-1,1u<<31};
+    uint64_t x = 88172645463325252ull; long bad = 0, n = 0;
+    for (uint32_t d : divs) {
+        iso::FastDiv f = iso::make_fastdiv(d);
+        const uint32_t edge[] = {0,1,d-1,d,d+1,2*d-1,2*d,0xFFFFFFFFu,0xFFFFFFFEu,0x80000000u,0x7FFFFFFFu};
+        for (uint32_t v : edge) { uint32_t q,r; iso::fast_divmod(v,f,q,r); bad += (q!=v/d)||(r!=v%d); ++n; }
+        for (int i = 0; i < 200000; ++i) {
+            x ^= x << 13; x ^= x >> 7; x ^= x << 17;
+            uint32_t v = (uint32_t)x; uint32_t q,r; iso::fast_divmod(v,f,q,r);
+            bad += (q!=v/d)||(r!=v%d); ++n;
+        }
+    }
+    std::printf("%ld %ld\n", n, bad);
+    return bad != 0;
+}
+"""
+
+
+def test_fastdiv_is_exact_on_the_host():
+    with tempfile.TemporaryDirectory() as td:
+        src = os.path.join(td, "t.cpp")
+        open(src, "w").write(FASTDIV_TEST)
+        exe = os.path.join(td, "t")
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-I",
+                               os.path.join(ROOT, "paper_1606_07676_amd", "csrc"), src, "-o", exe])
+        out = subprocess.check_output([exe], text=True).split()
+        assert int(out[0]) > 1_000_000 and int(out[1]) == 0
