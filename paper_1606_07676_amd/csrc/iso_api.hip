@@ -15,10 +15,6 @@ namespace {
 
 thread_local int g_last_hip_error = 0;
 
-// Launch shape of the round kernels (chosen by measurement on MI355X).
-constexpr int kUnroll = 4;
-constexpr bool kNonTemporal = false;
-constexpr bool kXcdRemap = false;
 constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per launch
 
 #define ISO_HIP_TRY(expr)                              \
@@ -33,8 +29,8 @@ constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per laun
 
 struct Launch {
     int kind;
-    uint32_t n_blocks;
     uint32_t grid;
+    bool lds_table;
     iso::ShiftArgs shift;
     iso::VectorArgs vec;
 };
@@ -74,26 +70,34 @@ int widest_vector(size_t m, std::initializer_list<const void *> ptrs) {
     return v;
 }
 
-void set_grid(Launch &l, uint32_t total) {
-    const uint32_t per_block = iso::kThreads * kUnroll;
-    l.n_blocks = (uint32_t)(((uint64_t)total + per_block - 1) / per_block);
-    const uint32_t per_xcd = (l.n_blocks + 7) / 8;
-    l.grid = kXcdRemap ? per_xcd * 8 : l.n_blocks;
+void set_grid(Launch &l, uint32_t total, uint32_t k) {
+    l.grid = (uint32_t)(((uint64_t)total + iso::kThreads - 1) / iso::kThreads);
+    l.lds_table = k <= iso::kLdsEntries;
     if (l.kind == ISO_ROUND_VECTOR) {
-        l.vec.total = total; l.vec.n_blocks = l.n_blocks; l.vec.blocks_per_xcd = per_xcd;
+        l.vec.total = total;
+        l.vec.k = k;
     } else {
-        l.shift.total = total; l.shift.n_blocks = l.n_blocks; l.shift.blocks_per_xcd = per_xcd;
+        l.shift.total = total;
+        l.shift.k = k;
     }
+}
+
+template <typename V, bool LDS>
+void enqueue(const Launch &l, hipStream_t stream) {
+    if (l.kind == ISO_ROUND_VECTOR)
+        hipLaunchKernelGGL((iso::vector_round_kernel<V, LDS>), dim3(l.grid), dim3(iso::kThreads), 0,
+                           stream, l.vec);
+    else
+        hipLaunchKernelGGL((iso::shift_round_kernel<V, LDS>), dim3(l.grid), dim3(iso::kThreads), 0,
+                           stream, l.shift);
 }
 
 template <typename V>
 int launch_one(const Launch &l, hipStream_t stream) {
-    if (l.kind == ISO_ROUND_VECTOR)
-        hipLaunchKernelGGL((iso::vector_round_kernel<V, kUnroll, kNonTemporal, kXcdRemap>),
-                           dim3(l.grid), dim3(iso::kThreads), 0, stream, l.vec);
+    if (l.lds_table)
+        enqueue<V, true>(l, stream);
     else
-        hipLaunchKernelGGL((iso::shift_round_kernel<V, kUnroll, kNonTemporal, kXcdRemap>),
-                           dim3(l.grid), dim3(iso::kThreads), 0, stream, l.shift);
+        enqueue<V, false>(l, stream);
     ISO_HIP_TRY(hipGetLastError());
     return ISO_SUCCESS;
 }
@@ -238,7 +242,7 @@ int init_common(int op, const void *sendbuf, void *recvbuf, size_t m, void *work
                 l.shift.d_inner = iso::make_fastdiv(l.shift.inner);
                 l.shift.d_pj = iso::make_fastdiv(l.shift.pj);
             }
-            set_grid(l, (uint32_t)(units_per_entry * k));
+            set_grid(l, (uint32_t)(units_per_entry * k), k);
             pending.push_back(pd);
             done += k;
         }
@@ -502,30 +506,29 @@ int iso_copy_reference(const void *src, void *dst, size_t bytes, void *hip_strea
     hipStream_t stream = (hipStream_t)hip_stream;
     const int vec = widest_vector(bytes, {src, dst});
     const uint64_t units = bytes / (size_t)vec;
-    const uint64_t per_block = (uint64_t)iso::kThreads * kUnroll;
-    const uint64_t blocks = (units + per_block - 1) / per_block;
+    const uint64_t blocks = (units + iso::kThreads - 1) / iso::kThreads;
     if (blocks > 0x7FFFFFFFull) return ISO_ERR_TOO_LARGE;
     const dim3 grid((uint32_t)blocks), block(iso::kThreads);
     switch (vec) {
         case 16:
-            hipLaunchKernelGGL((iso::copy_kernel<iso::vec16_t, kUnroll, kNonTemporal>), grid, block, 0,
-                               stream, (const iso::vec16_t *)src, (iso::vec16_t *)dst, units);
+            hipLaunchKernelGGL((iso::copy_kernel<iso::vec16_t>), grid, block, 0, stream,
+                               (const iso::vec16_t *)src, (iso::vec16_t *)dst, units);
             break;
         case 8:
-            hipLaunchKernelGGL((iso::copy_kernel<iso::vec8_t, kUnroll, kNonTemporal>), grid, block, 0,
-                               stream, (const iso::vec8_t *)src, (iso::vec8_t *)dst, units);
+            hipLaunchKernelGGL((iso::copy_kernel<iso::vec8_t>), grid, block, 0, stream,
+                               (const iso::vec8_t *)src, (iso::vec8_t *)dst, units);
             break;
         case 4:
-            hipLaunchKernelGGL((iso::copy_kernel<uint32_t, kUnroll, kNonTemporal>), grid, block, 0,
-                               stream, (const uint32_t *)src, (uint32_t *)dst, units);
+            hipLaunchKernelGGL((iso::copy_kernel<uint32_t>), grid, block, 0, stream,
+                               (const uint32_t *)src, (uint32_t *)dst, units);
             break;
         case 2:
-            hipLaunchKernelGGL((iso::copy_kernel<uint16_t, kUnroll, kNonTemporal>), grid, block, 0,
-                               stream, (const uint16_t *)src, (uint16_t *)dst, units);
+            hipLaunchKernelGGL((iso::copy_kernel<uint16_t>), grid, block, 0, stream,
+                               (const uint16_t *)src, (uint16_t *)dst, units);
             break;
         default:
-            hipLaunchKernelGGL((iso::copy_kernel<uint8_t, kUnroll, kNonTemporal>), grid, block, 0,
-                               stream, (const uint8_t *)src, (uint8_t *)dst, units);
+            hipLaunchKernelGGL((iso::copy_kernel<uint8_t>), grid, block, 0, stream,
+                               (const uint8_t *)src, (uint8_t *)dst, units);
             break;
     }
     ISO_HIP_TRY(hipGetLastError());

@@ -32,6 +32,8 @@ SMALL = [
     ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),
     ((37, 11), gen.moore(2, 2)),                          # several tiles, ragged tail
     ((1, 1), [(0, 0), (3, -2)]),                          # a single process
+    ((2, 2, 2, 2, 2), gen.moore(5, 1)),                   # 162 entries in one round: table too big for LDS
+    ((8, 4, 8), gen.moore(3, 3)),                         # s = 342, radius > 1, wrap-around aliases
 ]
 BLOCK_SIZES = [16, 48, 256, 1, 6, 20, 8, 1040]
 
