@@ -39,6 +39,19 @@ def parse():
     return ap.parse_args()
 
 
+def recorded_traffic(cfg_name, m):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
+    runs of this same command (counters cannot be read from inside the process).
+    Only the workload the summary was taken on gets a value; anything else: None."""
+    path = os.path.join(ROOT, "profiles", "shift_round_kernel_c2_hbm_traffic.txt")
+    if not (cfg_name.startswith("c2_") and m == 256 and os.path.exists(path)):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return int(line.split("=")[1])
+    return None
+
+
 def median(xs):
     xs = sorted(xs)
     n = len(xs)
@@ -183,7 +196,7 @@ def main():
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None,
+        "traffic": recorded_traffic(cfg.name, m),
         "algorithmic_bytes_per_launch": int(alg_bytes_per_launch),
         "avg_launch_us": round(avg_launch_ms * 1e3, 2),
         "launches_per_step": launches,

@@ -71,7 +71,17 @@ int widest_vector(size_t m, std::initializer_list<const void *> ptrs) {
 }
 
 void set_grid(Launch &l, uint32_t total, uint32_t k) {
-    l.grid = (uint32_t)(((uint64_t)total + iso::kThreads - 1) / iso::kThreads);
+    const uint32_t n_tiles = (uint32_t)(((uint64_t)total + iso::kThreads - 1) / iso::kThreads);
+    // Runs of 128 tiles (512 KiB of units) per XCD: measured best over the five workloads
+    // (no runs: -5 % where the rank stride is a multiple of 4 KiB; runs of 512 tiles or more:
+    // -8 % and worse, the last incomplete span leaves XCDs idle).
+    uint32_t run_log2 = 7;
+    while (run_log2 > 0 && (8u << run_log2) > n_tiles) --run_log2;
+    const uint32_t span = 8u << run_log2;
+    l.grid = (uint32_t)((((uint64_t)n_tiles + span - 1) / span) * span);
+    iso::TileMap &tm = l.kind == ISO_ROUND_VECTOR ? l.vec.map : l.shift.map;
+    tm.n_tiles = n_tiles;
+    tm.run_log2 = run_log2;
     l.lds_table = k <= iso::kLdsEntries;
     if (l.kind == ISO_ROUND_VECTOR) {
         l.vec.total = total;

@@ -47,8 +47,26 @@ struct alignas(16) DevEntry {
     uint32_t pad[3];
 };
 
+// Workgroup -> tile mapping.  The hardware hands consecutive workgroup ids to
+// the 8 XCDs round-robin; each XCD has its own L2.  `run_log2` makes XCD x work
+// on runs of 2^run_log2 consecutive tiles (tile = 256 consecutive units), the 8
+// XCDs' runs interleaved, so that one L2 sees consecutive ranks (all of its
+// channels are used even when the rank stride s*m is a multiple of the channel
+// interleave) while the 8 XCDs still sweep the same region of memory together.
+struct TileMap {
+    uint32_t n_tiles;      // tiles that carry work
+    uint32_t run_log2;
+};
+
+__device__ __forceinline__ bool tile_of_block(const TileMap &tm, uint32_t &tile) {
+    const uint32_t bid = blockIdx.x, x = bid & 7u, y = bid >> 3;
+    tile = ((y >> tm.run_log2) << (tm.run_log2 + 3)) + (x << tm.run_log2) + (y & ((1u << tm.run_log2) - 1u));
+    return tile < tm.n_tiles;
+}
+
 struct ShiftArgs {
     const DevEntry *entries;
+    TileMap map;
     uint32_t total;        // units in this launch = p * k * chunks
     uint32_t k;            // entries in this launch
     uint32_t inner;        // rank stride of the shifted dimension
@@ -59,6 +77,7 @@ struct ShiftArgs {
 struct VectorArgs {
     const DevEntry *entries;
     const uint32_t *offsets;   // [s][d] residues
+    TileMap map;
     uint32_t total;
     uint32_t k;
     int32_t d;
@@ -96,7 +115,9 @@ template <typename V, bool LDS>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
-    const uint32_t u = blockIdx.x * (uint32_t)kThreads + threadIdx.x;
+    uint32_t tile;
+    if (!tile_of_block(a.map, tile)) return;
+    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
@@ -116,7 +137,9 @@ template <typename V, bool LDS>
 __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
-    const uint32_t u = blockIdx.x * (uint32_t)kThreads + threadIdx.x;
+    uint32_t tile;
+    if (!tile_of_block(a.map, tile)) return;
+    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
