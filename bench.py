@@ -233,7 +233,7 @@ def main():
         extras = {}
         ksteps = max(5, K // 4)
         for name, alg in (("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM), ("sx_fused", iso.ISO_ALG_SX_FUSED),
-                          ("sx_rounds", iso.ISO_ALG_SX_ROUNDS)):
+                          ("sx_rounds", iso.ISO_ALG_SX_ROUNDS), ("onehop", iso.ISO_ALG_ONEHOP)):
             rs = [make_request(op, alg)[0] for op in ops]
             ms = time_steps(rs, ksteps, 3) / ksteps
             mv = sum(iso.iso_request_info(r)["bytes_read"] * 2 for r in rs)

@@ -63,7 +63,13 @@ enum iso_algorithm {
      * here one launch, per neighbour; s launches. */
     ISO_ALG_SX_ROUNDS      = 2,
     /* The same s exchanges issued as a single launch. */
-    ISO_ALG_SX_FUSED       = 3
+    ISO_ALG_SX_FUSED       = 3,
+    /* One-ported torus schedule (Sections 3.1-3.3, Algorithm 1 as printed): every
+     * round moves blocks one hop along one dimension; per dimension max c_j
+     * positive steps, then max -c_j negative steps, counted on the coordinates
+     * as given (not reduced modulo p_j).  D = sum_j (max+ + max-) launches,
+     * V = sum_i ||C^i||_1 block-moves per rank (all-to-all), W (allgather). */
+    ISO_ALG_ONEHOP         = 4
 };
 
 enum iso_buffer {                /* where a block sits during a schedule */
@@ -111,7 +117,7 @@ typedef struct {
 typedef struct {
     int32_t src_buf, src_slot;   /* enum iso_buffer, block index inside that buffer's row  */
     int32_t dst_buf, dst_slot;
-    int32_t shift;               /* SHIFT rounds: residue v in (0, p_j): the block comes
+    int32_t shift;               /* SHIFT rounds: residue v in [0, p_j): the block comes
                                     from the rank v steps back in `dim`; else 0            */
     int32_t neighbor;            /* index i of the offset whose route this move belongs to
                                     (allgather temporaries: -1); VECTOR rounds: source is

@@ -280,3 +280,89 @@ def replay_s_exchange_alltoall(dims, offsets, send):
     for i in range(len(offsets)):
         recv[tgt[:, i], i] = send[:, i]
     return recv
+
+
+def onehop_steps(offsets):
+    """The D communication steps of the one-ported torus schedules (Section 3.1,
+    Algorithm 1): per dimension j, first max_i c^i_j steps in the positive
+    direction, then max_i (-c^i_j) steps in the negative one.  List of
+    (j, direction, h)."""
+    offs = np.asarray(offsets, dtype=np.int64)
+    steps = []
+    if offs.size == 0:
+        return steps
+    for j in range(offs.shape[1]):
+        for h in range(int(max(0, offs[:, j].max()))):
+            steps.append((j, +1, h))
+        for h in range(int(max(0, (-offs[:, j]).max()))):
+            steps.append((j, -1, h))
+    return steps
+
+
+def replay_onehop_alltoall(dims, offsets, send, return_trace=False):
+    """One-ported torus all-to-all with alternating buffers (Algorithm 1).
+
+    hops[i] = ||C^i|| (raw coordinates).  In step h of dimension j, direction
+    +1, every block with c^i_j > h moves one hop to R (+) e_j (direction -1:
+    blocks with -c^i_j > h move to R (-) e_j).  It is received into the
+    intermediate buffer if hops[i] is even, into the receive buffer if odd, and
+    is sent from the send buffer on its very first hop, afterwards from the
+    buffer it was last received into.  (The printed algorithm names the send
+    buffer for every step of a block's first dimension; only the first hop can
+    be meant, since later steps must forward what the previous step delivered.)"""
+    send = np.asarray(send)
+    s = len(offsets)
+    offs = [tuple(int(c) for c in C) for C in offsets]
+    recvbuf, interbuf = np.zeros_like(send), np.zeros_like(send)
+    bufs = {"send": send, "recv": recvbuf, "inter": interbuf}
+    where = ["send"] * s
+    hops = [sum(abs(c) for c in C) for C in offs]
+    for i in range(s):
+        if hops[i] == 0:
+            recvbuf[:, i] = send[:, i]
+            where[i] = "recv"
+    trace = []
+    for (j, sign, h) in onehop_steps(offs):
+        parts = []
+        for i in range(s):
+            if sign * offs[i][j] > h:
+                parts.append((i, where[i], "inter" if hops[i] % 2 == 0 else "recv"))
+        landed = [(i, dst, _shift_push(bufs[src][:, i], dims, j, sign)) for i, src, dst in parts]
+        for i, dst, data in landed:
+            bufs[dst][:, i] = data
+            where[i] = dst
+            hops[i] -= 1
+        trace.append(((j, sign, h), parts))
+    assert all(x == 0 for x in hops) and all(w == "recv" for w in where)
+    return (recvbuf, trace) if return_trace else recvbuf
+
+
+def replay_onehop_allgather(dims, offsets, send, order=None, return_moves=False):
+    """One-ported torus allgather along the prefix trie (Section 3.2): in step h
+    of dimension order[t], direction +1, every trie node at level t whose edge
+    weight c exceeds h advances one hop (direction -1: -c > h).  Nodes start as
+    a copy of their parent's block; zero edges do not move."""
+    send = np.asarray(send)
+    p, s = send.shape[0], len(offsets)
+    offs = [tuple(int(c) for c in C) for C in offsets]
+    d = len(dims)
+    order = list(range(d)) if order is None else list(order)
+    node = {(): send}
+    moves = 0
+    for t in range(d):
+        j = order[t]
+        prefixes = sorted({tuple(C[order[u]] for u in range(t + 1)) for C in offs})
+        cur = {P: node[P[:-1]] for P in prefixes}
+        pos = max([P[-1] for P in prefixes] + [0])
+        neg = max([-P[-1] for P in prefixes] + [0])
+        for sign, count in ((+1, pos), (-1, neg)):
+            for h in range(count):
+                for P in prefixes:
+                    if sign * P[-1] > h:
+                        cur[P] = _shift_push(cur[P], dims, j, sign)
+                        moves += 1
+        node = cur
+    recv = np.empty((p, s) + send.shape[1:], dtype=send.dtype)
+    for i, C in enumerate(offs):
+        recv[:, i] = node[tuple(C[order[u]] for u in range(d))]
+    return (recv, moves) if return_moves else recv

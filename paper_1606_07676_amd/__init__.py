@@ -7,7 +7,7 @@ arguments.  PyTorch is used by callers for device memory and streams.
 from .binding import (  # noqa: F401
     IsoError, load_library, library_path,
     ISO_OP_ALLTOALL, ISO_OP_ALLGATHER,
-    ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED,
+    ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP,
     ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK,
     ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR,
     ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP,

@@ -14,7 +14,7 @@ ISO_MAX_DIMS = 16
 (ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP, ISO_ERR_NOMEM,
  ISO_ERR_TOO_LARGE, ISO_ERR_POINTER) = range(8)
 ISO_OP_ALLTOALL, ISO_OP_ALLGATHER = 0, 1
-ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED = 0, 1, 2, 3
+ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP = 0, 1, 2, 3, 4
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
 ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR = 0, 1, 2
 

@@ -1,13 +1,16 @@
 // Schedule builder for isomorphic sparse collectives (host only).
 //
-// All-to-all: Algorithm 1's alternating-buffer rule applied to the torus-direct
-// schedule of Section 5 (a block makes one hop per non-zero coordinate, and each
-// dimension has one round per distinct non-zero coordinate value).
-// Allgather: the prefix trie of Section 3.2, routed the same torus-direct way.
+// All-to-all: Algorithm 1's alternating-buffer rule, applied either to the
+// torus-direct schedule of Section 5 (a block makes one hop per non-zero
+// coordinate; each dimension has one round per distinct non-zero coordinate
+// value) or to the one-ported torus schedule of Section 3.1 (one hop per unit
+// of coordinate; positive steps, then negative steps, per dimension).
+// Allgather: the prefix trie of Section 3.2, routed the same two ways.
 // S-exchange: the straightforward algorithm of Section 3's first listing.
 #include "iso_plan.hpp"
 
 #include <algorithm>
+#include <cstdlib>
 #include <functional>
 #include <numeric>
 #include <queue>
@@ -64,46 +67,86 @@ int build_comm(int d, const int32_t *dims, int s, const int32_t *rel, Comm &out)
     return ISO_SUCCESS;
 }
 
-static iso_plan_entry_t mk(int sb, int ss, int db, int ds, int shift, int nb) {
+namespace {
+
+iso_plan_entry_t mk(int sb, int ss, int db, int ds, int shift, int nb) {
     iso_plan_entry_t e;
     e.src_buf = sb; e.src_slot = ss; e.dst_buf = db; e.dst_slot = ds;
     e.shift = shift; e.neighbor = nb;
     return e;
 }
 
+// Coordinates as the schedule sees them: residues (torus-direct) or the raw signed
+// values (one-hop, where |c| is the number of hops and the sign the direction).
+struct Coords {
+    const Comm &c;
+    bool raw;
+    int32_t at(int i, int j) const { return raw ? c.raw[(size_t)i * c.d + j] : c.c(i, j); }
+    bool zero(int i) const {
+        for (int j = 0; j < c.d; ++j)
+            if (at(i, j)) return false;
+        return true;
+    }
+};
+
+// residue that means "one step back" (direction +1) or "one step forward" (-1)
+int32_t unit_shift(const Comm &c, int j, int sign) {
+    const int32_t pj = c.dims[j];
+    return sign > 0 ? 1 % pj : (pj - 1) % pj;
+}
+
+bool by_dst(const iso_plan_entry_t &a, const iso_plan_entry_t &b) {
+    return a.dst_buf != b.dst_buf ? a.dst_buf < b.dst_buf : a.dst_slot < b.dst_slot;
+}
+
 // ---------------------------------------------------------------------------
 // all-to-all, message-combining
 // ---------------------------------------------------------------------------
-static void plan_alltoall_combined(const Comm &c, bool by_dim, Plan &pl) {
-    const int s = c.s, d = c.d;
-    std::vector<int> hops(s), where(s, ISO_BUF_SEND), wslot(s, -1);
+struct AlltoallState {
+    std::vector<int> hops, where, wslot;
+    int slot_in(int buf, int i) const { return buf == ISO_BUF_WORK ? wslot[i] : i; }
+    // one hop of block i: parity rule of Algorithm 1
+    iso_plan_entry_t hop(int i, int shift) {
+        // received into the receive buffer when an odd number of hops remains,
+        // so that the last hop (one remaining) always lands there
+        const int dst = (hops[i] % 2 == 0) ? ISO_BUF_WORK : ISO_BUF_RECV;
+        const int src = where[i];
+        iso_plan_entry_t e = mk(src, slot_in(src, i), dst, slot_in(dst, i), shift, i);
+        where[i] = dst;
+        --hops[i];
+        return e;
+    }
+};
+
+void alltoall_prologue(const Comm &c, const Coords &co, AlltoallState &st, Plan &pl) {
+    const int s = c.s;
+    st.hops.assign(s, 0);
+    st.where.assign(s, ISO_BUF_SEND);
+    st.wslot.assign(s, -1);
     int nwork = 0;
     Round self;
     self.kind = ISO_ROUND_SELF;
     for (int i = 0; i < s; ++i) {
-        hops[i] = c.nnz(i);
-        if (hops[i] >= 2) wslot[i] = nwork++;           // only these ever sit in the intermediate buffer
-        if (hops[i] == 0) self.entries.push_back(mk(ISO_BUF_SEND, i, ISO_BUF_RECV, i, 0, i));
+        for (int j = 0; j < c.d; ++j) st.hops[i] += co.raw ? std::abs(co.at(i, j)) : (co.at(i, j) != 0);
+        if (st.hops[i] >= 2) st.wslot[i] = nwork++;     // only these ever sit in the intermediate buffer
+        if (st.hops[i] == 0) self.entries.push_back(mk(ISO_BUF_SEND, i, ISO_BUF_RECV, i, 0, i));
     }
     pl.work_slots = nwork;
     if (!self.entries.empty()) pl.rounds.push_back(std::move(self));
-    auto slot_in = [&](int buf, int i) { return buf == ISO_BUF_WORK ? wslot[i] : i; };
-    for (int j = 0; j < d; ++j) {
+}
+
+void plan_alltoall_combined(const Comm &c, bool by_dim, Plan &pl) {
+    const Coords co{c, false};
+    AlltoallState st;
+    alltoall_prologue(c, co, st, pl);
+    for (int j = 0; j < c.d; ++j) {
         Round dim_round;
         dim_round.dim = j;
         for (int32_t v : c.values[j]) {
             Round r;
             r.dim = j;
-            for (int i = 0; i < s; ++i) {
-                if (c.c(i, j) != v) continue;
-                // received into the receive buffer when an odd number of hops remains,
-                // so that the last hop (one remaining) always lands there
-                const int dst = (hops[i] % 2 == 0) ? ISO_BUF_WORK : ISO_BUF_RECV;
-                const int src = where[i];
-                r.entries.push_back(mk(src, slot_in(src, i), dst, slot_in(dst, i), v, i));
-                where[i] = dst;
-                --hops[i];
-            }
+            for (int i = 0; i < c.s; ++i)
+                if (c.c(i, j) == v) r.entries.push_back(st.hop(i, v));
             if (by_dim)
                 dim_round.entries.insert(dim_round.entries.end(), r.entries.begin(), r.entries.end());
             else
@@ -119,38 +162,57 @@ static void plan_alltoall_combined(const Comm &c, bool by_dim, Plan &pl) {
     }
 }
 
+void plan_alltoall_onehop(const Comm &c, Plan &pl) {
+    const Coords co{c, true};
+    AlltoallState st;
+    alltoall_prologue(c, co, st, pl);
+    for (int j = 0; j < c.d; ++j)
+        for (int sign = +1; sign >= -1; sign -= 2) {            // positive steps, then negative
+            int32_t most = 0;
+            for (int i = 0; i < c.s; ++i) most = std::max(most, sign * co.at(i, j));
+            for (int32_t h = 0; h < most; ++h) {
+                Round r;
+                r.dim = j;
+                for (int i = 0; i < c.s; ++i)
+                    if (sign * co.at(i, j) > h) r.entries.push_back(st.hop(i, unit_shift(c, j, sign)));
+                pl.rounds.push_back(std::move(r));
+            }
+        }
+}
+
 // ---------------------------------------------------------------------------
 // allgather, message-combining along the prefix trie
 // ---------------------------------------------------------------------------
-namespace {
 struct Node {
     int parent;        // node index, -1 for the root
     int level;         // index into the dimension order; root: -1
-    int32_t value;     // residue on the edge from the parent
+    int32_t value;     // coordinate on the edge from the parent
     int first, last;   // range [first, last) of the sorted neighbour list below this node
     int store;         // nearest node on the path to the root (incl. self) that holds a copy
     int buf, slot;     // where that copy sits (stored nodes only; root: send block)
+    int tmp_slot;      // one-hop, |value| >= 2: second workspace slot the block alternates through
     int last_read;     // last level at which a child reads this copy
     std::vector<int> terminals;  // neighbours equal to this prefix padded with zeros
 };
-}  // namespace
 
-static void build_trie(const Comm &c, const std::vector<int32_t> &order,
-                       std::vector<int> &sorted, std::vector<Node> &nodes) {
-    const int s = c.s, d = c.d;
+void build_trie(const Coords &co, const std::vector<int32_t> &order, std::vector<int> &sorted,
+                std::vector<Node> &nodes) {
+    const int s = co.c.s, d = co.c.d;
     sorted.resize(s);
     std::iota(sorted.begin(), sorted.end(), 0);
+    // zero first, then by value: neighbours that end at a node head its range
+    auto key = [](int32_t v) { return std::make_pair(v != 0, v); };
     std::stable_sort(sorted.begin(), sorted.end(), [&](int a, int b) {
         for (int t = 0; t < d; ++t) {
-            int32_t x = c.c(a, order[t]), y = c.c(b, order[t]);
-            if (x != y) return x < y;
+            int32_t x = co.at(a, order[t]), y = co.at(b, order[t]);
+            if (x != y) return key(x) < key(y);
         }
         return false;
     });
     nodes.clear();
     Node root{};
     root.parent = -1; root.level = -1; root.value = 0; root.first = 0; root.last = s;
-    root.store = 0; root.buf = ISO_BUF_SEND; root.slot = 0; root.last_read = -1;
+    root.store = 0; root.buf = ISO_BUF_SEND; root.slot = 0; root.tmp_slot = -1; root.last_read = -1;
     nodes.push_back(root);
     size_t level_begin = 0, level_end = 1;
     for (int t = 0; t < d; ++t) {
@@ -159,19 +221,19 @@ static void build_trie(const Comm &c, const std::vector<int32_t> &order,
             int a = nodes[n].first;
             const int end = nodes[n].last;
             while (a < end) {
-                const int32_t v = c.c(sorted[a], j);
+                const int32_t v = co.at(sorted[a], j);
                 int b = a;
-                while (b < end && c.c(sorted[b], j) == v) ++b;
+                while (b < end && co.at(sorted[b], j) == v) ++b;
                 Node ch{};
                 ch.parent = (int)n; ch.level = t; ch.value = v; ch.first = a; ch.last = b;
-                ch.buf = -1; ch.slot = -1; ch.last_read = -1;
+                ch.buf = -1; ch.slot = -1; ch.tmp_slot = -1; ch.last_read = -1;
                 ch.store = v ? (int)nodes.size() : nodes[n].store;
                 if (v) {
-                    // neighbours that end here: all later coordinates zero; zero sorts first
+                    // neighbours that end here: all later coordinates zero; they sort first
                     for (int q = a; q < b; ++q) {
                         bool rest_zero = true;
                         for (int u = t + 1; u < d && rest_zero; ++u)
-                            rest_zero = c.c(sorted[q], order[u]) == 0;
+                            rest_zero = co.at(sorted[q], order[u]) == 0;
                         if (!rest_zero) break;
                         ch.terminals.push_back(sorted[q]);
                     }
@@ -185,14 +247,19 @@ static void build_trie(const Comm &c, const std::vector<int32_t> &order,
     }
 }
 
-static int64_t trie_moves(const std::vector<Node> &nodes) {
+// block-moves per rank: one per hop of every stored node, plus one per repeated neighbour
+int64_t trie_moves(const std::vector<Node> &nodes, bool per_hop) {
     int64_t n = 0;
     for (const Node &nd : nodes)
-        if (nd.level >= 0 && nd.value) n += nd.terminals.empty() ? 1 : (int64_t)nd.terminals.size();
+        if (nd.level >= 0 && nd.value) {
+            n += per_hop ? std::abs(nd.value) : 1;
+            if (nd.terminals.size() > 1) n += (int64_t)nd.terminals.size() - 1;
+        }
     return n;
 }
 
-std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
+std::vector<int32_t> pick_dim_order(const Coords &co, int64_t *moves_out) {
+    const Comm &c = co.c;
     const int d = c.d;
     std::vector<int32_t> ident(d), heur(d);
     std::iota(ident.begin(), ident.end(), 0);
@@ -202,7 +269,7 @@ std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
     std::vector<int> distinct(d), maxmult(d, 0);
     for (int j = 0; j < d; ++j) {
         std::vector<int32_t> col(c.s);
-        for (int i = 0; i < c.s; ++i) col[i] = c.c(i, j);
+        for (int i = 0; i < c.s; ++i) col[i] = co.at(i, j);
         std::sort(col.begin(), col.end());
         int run = 0;
         distinct[j] = 0;
@@ -217,12 +284,12 @@ std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
     });
     std::vector<int> sorted;
     std::vector<Node> nodes;
-    build_trie(c, ident, sorted, nodes);
-    const int64_t mi = trie_moves(nodes);
+    build_trie(co, ident, sorted, nodes);
+    const int64_t mi = trie_moves(nodes, co.raw);
     int64_t mh = mi;
     if (heur != ident) {
-        build_trie(c, heur, sorted, nodes);
-        mh = trie_moves(nodes);
+        build_trie(co, heur, sorted, nodes);
+        mh = trie_moves(nodes, co.raw);
     }
     if (mh < mi) {
         if (moves_out) *moves_out = mh;
@@ -232,30 +299,30 @@ std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
     return ident;
 }
 
-static void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
-    const int s = c.s, d = c.d;
-    pl.dim_order = allgather_dim_order(c, nullptr);
-    std::vector<int> sorted;
-    std::vector<Node> nodes;
-    build_trie(c, pl.dim_order, sorted, nodes);
-
-    Round self;
-    self.kind = ISO_ROUND_SELF;
-    for (int i = 0; i < s; ++i)
-        if (c.nnz(i) == 0) self.entries.push_back(mk(ISO_BUF_SEND, 0, ISO_BUF_RECV, i, 0, i));
-    if (!self.entries.empty()) pl.rounds.push_back(std::move(self));
-
-    // which copies are read at which level
+// Where every stored node keeps its copy: the receive slot of a neighbour that
+// ends at the node, else a workspace slot; workspace slots are handed out again
+// once the level of their last reader has passed.  One-hop nodes with two or
+// more hops also get a second slot for the duration of their own level.
+int assign_storage(std::vector<Node> &nodes, int d, bool per_hop) {
     for (size_t n = 1; n < nodes.size(); ++n)
         if (nodes[n].value) {
             Node &src = nodes[nodes[nodes[n].parent].store];
             src.last_read = std::max(src.last_read, nodes[n].level);
         }
-    // storage: receive slot when the prefix is itself a neighbour, else a workspace
-    // slot that is reused once every reader's level has passed
     std::priority_queue<int, std::vector<int>, std::greater<int>> free_slots;
-    std::vector<std::pair<int, int>> live;   // (last_read level, slot)
+    std::vector<std::pair<int, int>> live;   // (last level that reads it, slot)
     int nwork = 0;
+    auto take = [&](int last_read) {
+        int slot;
+        if (free_slots.empty()) {
+            slot = nwork++;
+        } else {
+            slot = free_slots.top();
+            free_slots.pop();
+        }
+        live.emplace_back(last_read, slot);
+        return slot;
+    };
     size_t n = 1;
     for (int t = 0; t < d; ++t) {
         for (size_t q = 0; q < live.size();) {
@@ -275,22 +342,33 @@ static void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
                 nd.slot = nd.terminals[0];
             } else {
                 nd.buf = ISO_BUF_WORK;
-                if (free_slots.empty()) {
-                    nd.slot = nwork++;
-                } else {
-                    nd.slot = free_slots.top();
-                    free_slots.pop();
-                }
-                live.emplace_back(nd.last_read, nd.slot);
+                nd.slot = take(nd.last_read);
             }
+            if (per_hop && std::abs(nd.value) >= 2) nd.tmp_slot = take(t);
         }
     }
-    pl.work_slots = nwork;
+    return nwork;
+}
 
-    auto by_dst = [](const iso_plan_entry_t &a, const iso_plan_entry_t &b) {
-        return a.dst_buf != b.dst_buf ? a.dst_buf < b.dst_buf : a.dst_slot < b.dst_slot;
-    };
-    n = 1;
+void allgather_self_round(const Coords &co, Plan &pl) {
+    Round self;
+    self.kind = ISO_ROUND_SELF;
+    for (int i = 0; i < co.c.s; ++i)
+        if (co.zero(i)) self.entries.push_back(mk(ISO_BUF_SEND, 0, ISO_BUF_RECV, i, 0, i));
+    if (!self.entries.empty()) pl.rounds.push_back(std::move(self));
+}
+
+void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
+    const Coords co{c, false};
+    const int d = c.d;
+    pl.dim_order = pick_dim_order(co, nullptr);
+    std::vector<int> sorted;
+    std::vector<Node> nodes;
+    build_trie(co, pl.dim_order, sorted, nodes);
+    allgather_self_round(co, pl);
+    pl.work_slots = assign_storage(nodes, d, false);
+
+    size_t n = 1;
     for (int t = 0; t < d; ++t) {
         const int j = pl.dim_order[t];
         const size_t lvl_begin = n;
@@ -324,10 +402,66 @@ static void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
     }
 }
 
+void plan_allgather_onehop(const Comm &c, Plan &pl) {
+    const Coords co{c, true};
+    const int d = c.d;
+    pl.dim_order = pick_dim_order(co, nullptr);
+    std::vector<int> sorted;
+    std::vector<Node> nodes;
+    build_trie(co, pl.dim_order, sorted, nodes);
+    allgather_self_round(co, pl);
+    pl.work_slots = assign_storage(nodes, d, true);
+
+    // where a node's block sits while it travels: parent's copy before the first hop
+    std::vector<std::pair<int, int>> at(nodes.size());
+    size_t n = 1;
+    for (int t = 0; t < d; ++t) {
+        const int j = pl.dim_order[t];
+        const size_t lvl_begin = n;
+        while (n < nodes.size() && nodes[n].level == t) ++n;
+        for (size_t q = lvl_begin; q < n; ++q) {
+            const Node &src = nodes[nodes[nodes[q].parent].store];
+            at[q] = {src.buf, src.slot};
+        }
+        for (int sign = +1; sign >= -1; sign -= 2) {
+            int32_t most = 0;
+            for (size_t q = lvl_begin; q < n; ++q) most = std::max(most, sign * nodes[q].value);
+            for (int32_t h = 0; h < most; ++h) {
+                Round r;
+                r.dim = j;
+                const int32_t shift = unit_shift(c, j, sign);
+                for (size_t q = lvl_begin; q < n; ++q) {
+                    const Node &nd = nodes[q];
+                    if (sign * nd.value <= h) continue;
+                    const int32_t remaining = sign * nd.value - h;
+                    // odd number of hops left: into the node's own place, else the spare slot
+                    if (remaining == 1) {
+                        if (nd.terminals.empty()) {
+                            r.entries.push_back(mk(at[q].first, at[q].second, nd.buf, nd.slot, shift, -1));
+                        } else {
+                            for (int i : nd.terminals)
+                                r.entries.push_back(mk(at[q].first, at[q].second, ISO_BUF_RECV, i, shift, i));
+                        }
+                        at[q] = {nd.buf, nd.slot};
+                    } else {
+                        const std::pair<int, int> dst = remaining % 2 ? std::make_pair(nd.buf, nd.slot)
+                                                                      : std::make_pair((int)ISO_BUF_WORK, nd.tmp_slot);
+                        r.entries.push_back(mk(at[q].first, at[q].second, dst.first, dst.second, shift,
+                                               nd.terminals.empty() ? -1 : nd.terminals[0]));
+                        at[q] = dst;
+                    }
+                }
+                std::stable_sort(r.entries.begin(), r.entries.end(), by_dst);
+                pl.rounds.push_back(std::move(r));
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // straightforward s-exchange
 // ---------------------------------------------------------------------------
-static void plan_s_exchange(const Comm &c, int op, bool fused, Plan &pl) {
+void plan_s_exchange(const Comm &c, int op, bool fused, Plan &pl) {
     Round all;
     all.kind = ISO_ROUND_VECTOR;
     for (int i = 0; i < c.s; ++i) {
@@ -342,6 +476,12 @@ static void plan_s_exchange(const Comm &c, int op, bool fused, Plan &pl) {
         }
     }
     if (fused && !all.entries.empty()) pl.rounds.push_back(std::move(all));
+}
+
+}  // namespace
+
+std::vector<int32_t> allgather_dim_order(const Comm &c, int64_t *moves_out) {
+    return pick_dim_order(Coords{c, false}, moves_out);
 }
 
 int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
@@ -359,6 +499,12 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
                 plan_alltoall_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
             else
                 plan_allgather_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
+            break;
+        case ISO_ALG_ONEHOP:
+            if (op == ISO_OP_ALLTOALL)
+                plan_alltoall_onehop(c, pl);
+            else
+                plan_allgather_onehop(c, pl);
             break;
         case ISO_ALG_SX_ROUNDS:
         case ISO_ALG_SX_FUSED:

@@ -16,8 +16,9 @@ from oracle import c_twin
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
-ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused"}
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
+        iso.ISO_ALG_ONEHOP]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop"}
 
 SMALL = [
     ((5,), [(1,), (-2,), (7,)]),
@@ -108,7 +109,9 @@ def test_restart_and_side_stream_give_the_same_result():
     for alg in ALGS:
         recv, info = _run(cfg.dims, cfg.offsets, iso.ISO_OP_ALLTOALL, alg, cfg.m, send, stream=side, starts=3)
         assert np.array_equal(recv.cpu().numpy(), want)
-    assert info["launches"] == 1
+        assert info["launches"] == {iso.ISO_ALG_COMBINED: 4, iso.ISO_ALG_COMBINED_BYDIM: 2,
+                                    iso.ISO_ALG_SX_ROUNDS: 8, iso.ISO_ALG_SX_FUSED: 1,
+                                    iso.ISO_ALG_ONEHOP: 4}[alg]
 
 
 def test_noop_and_error_paths():
@@ -223,6 +226,10 @@ def test_named_workloads_full_size(key, alg):
                 moves = (orc.direct_alltoall_volume(cfg.dims, cfg.offsets) if op == iso.ISO_OP_ALLTOALL
                          else orc.direct_allgather_volume(cfg.dims, cfg.offsets))
                 assert info["bytes_read"] == moves * cfg.p * m == info["bytes_written"]
+            if alg == iso.ISO_ALG_ONEHOP:
+                assert info["launches"] == orc.onehop_rounds(cfg.offsets)
+                if op == iso.ISO_OP_ALLTOALL:
+                    assert info["bytes_read"] == orc.onehop_alltoall_volume(cfg.offsets) * cfg.p * m
     # a second seed on the combined path
     if alg == iso.ISO_ALG_COMBINED:
         _check_full(cfg, _ops(cfg)[0], alg, cfg.m, seed=77 + key, host_oracle=False)

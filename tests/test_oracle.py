@@ -314,3 +314,35 @@ def test_c_twin_config1_against_roll():
     for i, C in enumerate(cfg.offsets):
         want = np.roll(send[:, i].reshape(cfg.dims + (cfg.m,)), C, axis=(0, 1)).reshape(cfg.p, cfg.m)
         assert np.array_equal(got[:, i], want)
+
+
+# ---------------------------------------------------------------- one-hop torus schedules
+
+@pytest.mark.parametrize("dims,offsets", TORI)
+def test_onehop_schedules_reach_the_definition(dims, offsets):
+    p, s = int(np.prod(dims)), len(offsets)
+    send = _rand_send(p, s, 3)
+    keep = send.copy()
+    recv, trace = orc.replay_onehop_alltoall(dims, offsets, send, return_trace=True)
+    assert np.array_equal(recv, orc.alltoall(dims, offsets, send))
+    assert np.array_equal(send, keep)
+    # Proposition 1: D steps, V block-moves, every step moves at least one block
+    assert len(trace) == orc.onehop_rounds(offsets) == len(orc.onehop_steps(offsets))
+    assert sum(len(parts) for _, parts in trace) == orc.onehop_alltoall_volume(offsets)
+    assert all(parts for _, parts in trace)
+    one = np.ascontiguousarray(send[:, 0])
+    got, moves = orc.replay_onehop_allgather(dims, offsets, one, return_moves=True)
+    assert np.array_equal(got, orc.allgather(dims, offsets, one))
+    # Proposition 2: W block-moves, W <= V
+    assert moves == orc.onehop_allgather_volume(offsets) <= orc.onehop_alltoall_volume(offsets)
+
+
+def test_onehop_figure1_counts(golden):
+    offs = [tuple(_ints(t)) for t in golden["fig1_offsets"].split(";")]
+    dims = (6, 5, 4)
+    send = _rand_send(120, 10, 2)
+    _, trace = orc.replay_onehop_alltoall(dims, offs, send, return_trace=True)
+    assert len(trace) == int(golden["fig1_onehop_D"])
+    assert sum(len(p) for _, p in trace) == int(golden["fig1_onehop_V"])
+    _, moves = orc.replay_onehop_allgather(dims, offs, send[:, 0], return_moves=True)
+    assert moves == int(golden["fig1_onehop_W"])

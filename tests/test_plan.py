@@ -31,7 +31,8 @@ CASES = [
     ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),     # repeats
     ((3, 3), []),                                                         # empty neighbourhood
 ]
-ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
+        iso.ISO_ALG_ONEHOP]
 
 
 def test_library_exports_every_declared_symbol():
@@ -118,7 +119,7 @@ def _replay(dims, offsets, op, rounds, work_slots, send, m):
         for e in entries:
             src = bufs[e["src_buf"]][..., e["src_slot"], :]
             if info["kind"] == iso.ISO_ROUND_SHIFT:
-                assert 0 < e["shift"] < dims[info["dim"]]
+                assert 0 <= e["shift"] < dims[info["dim"]]      # 0 only on a ring of one process
                 data = np.roll(src, e["shift"], axis=info["dim"])
             elif info["kind"] == iso.ISO_ROUND_SELF:
                 data = src.copy()
@@ -168,6 +169,16 @@ def test_alltoall_plan_reaches_the_oracle_result(dims, offsets, alg):
         else:
             assert len(shift_rounds) == len({j for j, _ in orc.direct_rounds(dims, offsets)})
         assert len(rounds) - len(shift_rounds) == (1 if n_self else 0)
+    elif alg == iso.ISO_ALG_ONEHOP:
+        # Proposition 1: D steps of one hop each, V = sum of 1-norms block-moves (raw coordinates)
+        raw_self = sum(1 for C in offsets if not any(C))
+        shift_rounds = [r for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT]
+        assert len(shift_rounds) == orc.onehop_rounds(offsets)
+        assert pinfo["entries"] == orc.onehop_alltoall_volume(offsets) + raw_self
+        assert [(r[0]["dim"]) for r in shift_rounds] == [j for j, _, _ in orc.onehop_steps(offsets)]
+        for info, entries in shift_rounds:
+            pj = dims[info["dim"]]
+            assert {e["shift"] for e in entries} <= {1 % pj, (pj - 1) % pj} and entries
     else:
         assert pinfo["entries"] == s and pinfo["work_slots"] == 0
         assert len(rounds) == (s if alg == iso.ISO_ALG_SX_ROUNDS else min(s, 1))
@@ -196,6 +207,16 @@ def test_allgather_plan_reaches_the_oracle_result(dims, offsets, alg):
         if alg == iso.ISO_ALG_COMBINED:
             n_shift = sum(1 for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT)
             assert n_shift == len(orc.direct_rounds(dims, offsets))
+    elif alg == iso.ISO_ALG_ONEHOP:
+        # Proposition 2: the same D steps, W block-moves (plus one per repeated offset)
+        order = pinfo["dim_order"][:len(dims)]
+        raw = [tuple(C) for C in offsets]
+        raw_self = sum(1 for C in raw if not any(C))
+        dup_extra = sum(raw[:i].count(C) > 0 and any(C) for i, C in enumerate(raw))
+        n_shift = sum(1 for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT)
+        assert n_shift == orc.onehop_rounds(offsets)
+        assert pinfo["entries"] == orc.onehop_allgather_volume(offsets, order) + dup_extra + raw_self
+        assert pinfo["entries"] - raw_self - dup_extra <= orc.onehop_alltoall_volume(offsets)
 
 
 def test_figure1_example_plan(golden):
