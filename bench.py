@@ -248,6 +248,13 @@ def main():
             extras[f"combined_{op_name[op]}_only"] = {
                 "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
                 "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+        for r in reqs:                                  # the same requests replayed as HIP graphs
+            iso.iso_request_set_graph(r, True)
+        ms = time_steps(reqs, ksteps, 3) / ksteps
+        extras["combined_graph"] = {"ms_per_step": round(ms, 5), "delivered_GBs": round(delivered / ms / 1e6, 1),
+                                    "moved_GBs": round(moved / ms / 1e6, 1), "launches": len(reqs)}
+        for r in reqs:
+            iso.iso_request_set_graph(r, False)
         nb = 1 << 30
         a = torch.empty(nb, dtype=torch.uint8, device=dev)
         b = torch.empty(nb, dtype=torch.uint8, device=dev)

@@ -200,6 +200,13 @@ int iso_start(iso_request_t req, void *hip_stream);
  * order (0 <= first, first+count <= launches of iso_request_info).  For timing
  * individual rounds; running all ranges in order equals one iso_start. */
 int iso_start_range(iso_request_t req, int first, int count, void *hip_stream);
+/* enable != 0: records the request's launch sequence once into a HIP graph (one
+ * kernel node per round, chained; allocates the graph on first use) and makes
+ * every later iso_start replay that graph with a single hipGraphLaunch -- the
+ * persistent request of Section 2 taken one step further, for collectives whose
+ * cost is dominated by the per-round start-up.  enable == 0: back to individual
+ * launches.  iso_start_range is unaffected.  The result is the same either way. */
+int iso_request_set_graph(iso_request_t req, int enable);
 /* Blocks the host until the most recent iso_start of this request completed
  * (Section 7's proposed completion call). */
 int iso_wait(iso_request_t req);

@@ -91,6 +91,7 @@ _PROTOTYPES = {
     "iso_neighbor_allgather_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_start": ([_VP, _VP], _I),
     "iso_start_range": ([_VP, _I, _I, _VP], _I),
+    "iso_request_set_graph": ([_VP, _I], _I),
     "iso_wait": ([_VP], _I),
     "iso_request_info": ([_VP, ctypes.POINTER(iso_request_info_t)], _I),
     "iso_request_plan": ([_VP, ctypes.POINTER(_VP)], _I),
@@ -293,6 +294,10 @@ def iso_start(req, stream=None):
 def iso_start_range(req, first, count, stream=None):
     _check(load_library().iso_start_range(req.handle, first, count, _stream_handle(stream)),
            "iso_start_range")
+
+
+def iso_request_set_graph(req, enable=True):
+    _check(load_library().iso_request_set_graph(req.handle, 1 if enable else 0), "iso_request_set_graph")
 
 
 def iso_wait(req):

@@ -140,6 +140,9 @@ struct iso_request_s {
     std::vector<Launch> launches;
     hipStream_t last_stream = nullptr;
     bool started = false;
+    hipGraph_t graph = nullptr;          // the launches of one collective as a HIP graph
+    hipGraphExec_t graph_exec = nullptr;
+    bool use_graph = false;
 };
 
 namespace {
@@ -428,9 +431,54 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m, vo
     });
 }
 
+int iso_request_set_graph(iso_request_t req, int enable) {
+    if (!req) return ISO_ERR_ARG;
+    if (!enable || req->launches.empty()) {
+        req->use_graph = false;
+        return ISO_SUCCESS;
+    }
+    if (!req->graph_exec) {
+        // record the launch sequence once on a private stream, then replay it
+        hipStream_t cs = nullptr;
+        ISO_HIP_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
+        hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed);
+        int st = ISO_SUCCESS;
+        if (e == hipSuccess) {
+            for (const Launch &l : req->launches)
+                if ((st = launch_width(req->info.vector_bytes, l, cs)) != ISO_SUCCESS) break;
+            hipGraph_t g = nullptr;
+            e = hipStreamEndCapture(cs, &g);
+            if (e == hipSuccess && st == ISO_SUCCESS) {
+                e = hipGraphInstantiate(&req->graph_exec, g, nullptr, nullptr, 0);
+                req->graph = g;
+            } else if (g) {
+                (void)hipGraphDestroy(g);
+            }
+        }
+        (void)hipStreamDestroy(cs);
+        if (st != ISO_SUCCESS) return st;
+        if (e != hipSuccess) {
+            if (req->graph) (void)hipGraphDestroy(req->graph);
+            req->graph = nullptr;
+            req->graph_exec = nullptr;
+            g_last_hip_error = (int)e;
+            (void)hipGetLastError();
+            return ISO_ERR_HIP;
+        }
+    }
+    req->use_graph = true;
+    return ISO_SUCCESS;
+}
+
 int iso_start(iso_request_t req, void *hip_stream) {
     if (!req) return ISO_ERR_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
+    if (req->use_graph) {
+        ISO_HIP_TRY(hipGraphLaunch(req->graph_exec, stream));
+        req->last_stream = stream;
+        req->started = true;
+        return ISO_SUCCESS;
+    }
     for (const Launch &l : req->launches) {
         int st = launch_width(req->info.vector_bytes, l, stream);
         if (st != ISO_SUCCESS) return st;
@@ -476,6 +524,8 @@ int iso_request_free(iso_request_t *req) {
     if (!req) return ISO_ERR_ARG;
     int st = ISO_SUCCESS;
     if (*req) {
+        if ((*req)->graph_exec) (void)hipGraphExecDestroy((*req)->graph_exec);
+        if ((*req)->graph) (void)hipGraphDestroy((*req)->graph);
         if ((*req)->dev_table) {
             hipError_t e = hipFree((*req)->dev_table);
             if (e != hipSuccess) {

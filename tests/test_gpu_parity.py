@@ -114,6 +114,52 @@ def test_restart_and_side_stream_give_the_same_result():
                                     iso.ISO_ALG_ONEHOP: 4}[alg]
 
 
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS],
+                         ids=lambda a: ALG_NAMES[a])
+def test_graph_replay_matches_eager_every_time(alg):
+    """The captured launch sequence is replayed several times, with eager work of this
+    program (fills, another eager collective) and synchronisations in between; every
+    replay must give the oracle's result."""
+    cases = [((8, 8), gen.moore(2, 1), 32, iso.ISO_OP_ALLTOALL),
+             ((9, 9, 9), SMALL[6][1], 48, iso.ISO_OP_ALLGATHER),
+             ((37, 11), gen.moore(2, 2), 256, iso.ISO_OP_ALLTOALL)]
+    side = torch.cuda.Stream()
+    for dims, offsets, m, op in cases:
+        p, s = int(np.prod(dims)), len(offsets)
+        comm = _comm(dims, offsets)
+        if op == iso.ISO_OP_ALLTOALL:
+            send_h = gen.alltoall_send(9, p, s, m)
+            want = orc.alltoall(dims, offsets, send_h)
+            init = iso.iso_neighbor_alltoall_init
+        else:
+            send_h = gen.allgather_send(9, p, m)
+            want = orc.allgather(dims, offsets, send_h)
+            init = iso.iso_neighbor_allgather_init
+        send = torch.from_numpy(send_h).to(DEV)
+        wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+        recv = torch.empty((p, s, m), dtype=torch.uint8, device=DEV)
+        work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        req = init(send, recv, m, work, comm, alg)
+        iso.iso_request_set_graph(req, True)
+        for rep in range(4):
+            recv.fill_(0xEE)                       # eager work between replays
+            work.fill_(0xDD)
+            other, _ = _run(dims, offsets, op, iso.ISO_ALG_SX_FUSED, m, send)     # an eager collective
+            torch.cuda.synchronize()
+            iso.iso_start(req, side if rep % 2 else None)
+            iso.iso_wait(req)
+            got = recv.cpu().numpy()
+            assert np.array_equal(got, want), f"replay {rep} dims={dims}"
+            assert np.array_equal(other.cpu().numpy(), want)
+        iso.iso_request_set_graph(req, False)      # and back to individual launches
+        recv.fill_(0)
+        torch.cuda.synchronize()
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        assert np.array_equal(recv.cpu().numpy(), want)
+        iso.iso_request_free(req)
+
+
 def test_noop_and_error_paths():
     comm = _comm((4, 4), gen.moore(2, 1))
     p, s, m = 16, 8, 32
