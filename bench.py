@@ -269,6 +269,28 @@ def main():
         torch.cuda.synchronize()
         extras["copy_1GiB_GBs_read_plus_write"] = round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
         del a, b
+        # irregular all-to-all in the shape of the paper's stencil experiment (Section 4): block of
+        # neighbour i has base^(d - ||C^i||_1) bytes; same torus, Moore radius 1, base 64
+        if cfg.d == 3 and args.config == "2":
+            offs = gen.moore(3, 1)
+            sizes = gen.stencil_block_sizes(offs, 64)
+            displs, ext = gen.packed_displacements(sizes, 16)
+            icomm = iso.iso_neighborhood_create(cfg.dims, offs)
+            isend = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
+            irecv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
+            for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("sx_fused", iso.ISO_ALG_SX_FUSED)):
+                wsb = iso.iso_workspace_bytes_v(icomm, iso.ISO_OP_ALLTOALL, alg, sizes)
+                iwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+                r = iso.iso_neighbor_alltoallv_init(isend, sizes, displs, ext, irecv, sizes, displs, ext,
+                                                    iwork, icomm, alg)
+                ms = time_steps([r], ksteps, 3) / ksteps
+                inf = iso.iso_request_info(r)
+                extras[f"alltoallv_stencil_base64_{name}"] = {
+                    "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
+                    "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+                iso.iso_request_free(r)
+                del iwork
+            del isend, irecv
         out["comparison"] = extras
         log(json.dumps(extras))
 

@@ -192,6 +192,34 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m,
                                 void *workspace, size_t workspace_bytes,
                                 iso_comm_t comm, int algorithm, iso_request_t *req);
 
+/* ---- irregular variants (Section 2, second interface listing) ---------------
+ * Per-neighbour block sizes and displacements, in bytes, the same on every
+ * rank; the paper's v and w variants differ only in MPI datatypes and collapse
+ * into this one byte-based form.  The same schedules are used (Section 4).
+ *   send_sizes/recv_sizes: host, s values; must be equal pairwise (ISO_ERR_ARG).
+ *   send_displs/recv_displs: host, s values: offset of block i inside a rank's row.
+ *   send_extent/recv_extent: bytes between the rows of consecutive ranks; every
+ *     block must lie inside its row (ISO_ERR_ARG); receive blocks must not
+ *     overlap each other (ISO_ERR_OVERLAP); send blocks may.
+ *   sendbuf: device, rank R's row starts at sendbuf + R*send_extent (read-only);
+ *   recvbuf: device, likewise; bytes of a row outside the s blocks are not touched.
+ * Blocks of size 0 are legal and move nothing.  Each block is moved in units of
+ * the widest power of two (<= 16 bytes) dividing its size, its addresses and the
+ * extents, so a 1-byte block next to a 16 KiB block does not narrow the latter.
+ * Workspace: iso_workspace_bytes_v().  Other rules as for the regular calls. */
+int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *sizes, size_t *bytes);
+int iso_neighbor_alltoallv_init(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                const size_t *recv_displs, size_t recv_extent, void *workspace,
+                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                iso_request_t *req);
+/* Allgather: every rank contributes one block of send_size bytes (its row starts at
+ * sendbuf + R*send_extent); recv_sizes must all equal send_size (ISO_ERR_ARG). */
+int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                 const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                 void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                 iso_request_t *req);
+
 /* Enqueues the launches of one collective on `hip_stream` (a hipStream_t; NULL
  * = the default stream) and returns without waiting.  Rounds are ordered by the
  * stream.  Calls on one request must not overlap in time on the device. */

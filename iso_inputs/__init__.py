@@ -7,7 +7,7 @@ the method's arithmetic: nothing here knows how a torus wraps, which rank is
 whose source, or what a schedule is.
 """
 from .neighborhoods import (moore, von_neumann, positive_octant, shales,
-                            random_distinct)
+                            random_distinct, stencil_block_sizes, packed_displacements)
 from .blocks import (mix32, block_words, block_bytes, block_bytes_torch,
                      ALLGATHER_TWEAK, alltoall_send, allgather_send,
                      block_words_torch, alltoall_send_torch,
@@ -16,6 +16,7 @@ from .configs import CONFIGS, Workload, get_config
 
 __all__ = [
     "moore", "von_neumann", "positive_octant", "shales", "random_distinct",
+    "stencil_block_sizes", "packed_displacements",
     "mix32", "block_words", "block_bytes", "block_bytes_torch", "ALLGATHER_TWEAK", "alltoall_send", "allgather_send",
     "block_words_torch", "alltoall_send_torch", "allgather_send_torch",
     "CONFIGS", "Workload", "get_config",

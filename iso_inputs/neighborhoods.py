@@ -64,3 +64,22 @@ def random_distinct(d, lo, hi, s, seed):
             seen.add(c)
             out.append(c)
     return out
+
+
+def stencil_block_sizes(offsets, base):
+    """Irregular block sizes of the paper's all-to-all-w experiment (Section 4):
+    neighbour i gets base ** (d - ||C^i||_1) bytes, as in a stencil code where
+    faces are larger than edges and edges larger than corners."""
+    d = len(offsets[0]) if offsets else 0
+    return [int(base) ** max(0, d - sum(abs(c) for c in C)) for C in offsets]
+
+
+def packed_displacements(sizes, align=16):
+    """Blocks laid out in neighbour order, each start rounded up to `align`
+    bytes; returns (displacements, extent)."""
+    displs, at = [], 0
+    for n in sizes:
+        at = (at + align - 1) // align * align
+        displs.append(at)
+        at += int(n)
+    return displs, (at + align - 1) // align * align

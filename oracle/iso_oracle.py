@@ -366,3 +366,29 @@ def replay_onehop_allgather(dims, offsets, send, order=None, return_moves=False)
     for i, C in enumerate(offs):
         recv[:, i] = node[tuple(C[order[u]] for u in range(d))]
     return (recv, moves) if return_moves else recv
+
+
+# ---------------------------------------------------------------------------
+# Part 4: irregular variants (Section 2, second interface listing): per-neighbour
+# block sizes and displacements, identical on all processes, send and receive
+# sizes equal pairwise
+# ---------------------------------------------------------------------------
+
+def alltoallv(dims, offsets, send_rows, sizes, send_displs, recv_rows, recv_displs):
+    """recv_rows[R][recv_displs[i] : +sizes[i]] = send_rows[R (-) C^i][send_displs[i] : +sizes[i]].
+    send_rows: uint8 (p, send_extent); recv_rows: uint8 (p, recv_extent), modified in
+    place and returned (bytes outside the s blocks keep their value)."""
+    src = source_ranks(dims, offsets)
+    for i in range(len(offsets)):
+        n = int(sizes[i])
+        recv_rows[:, recv_displs[i]:recv_displs[i] + n] = \
+            send_rows[src[:, i], send_displs[i]:send_displs[i] + n]
+    return recv_rows
+
+
+def allgatherv(dims, offsets, send_rows, size, recv_rows, recv_displs):
+    """recv_rows[R][recv_displs[i] : +size] = send_rows[R (-) C^i][0 : size]."""
+    src = source_ranks(dims, offsets)
+    for i in range(len(offsets)):
+        recv_rows[:, recv_displs[i]:recv_displs[i] + size] = send_rows[src[:, i], :size]
+    return recv_rows

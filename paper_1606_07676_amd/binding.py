@@ -89,6 +89,11 @@ _PROTOTYPES = {
     "iso_workspace_bytes": ([_VP, _I, _I, _SZ, ctypes.POINTER(_SZ)], _I),
     "iso_neighbor_alltoall_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgather_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
+    "iso_workspace_bytes_v": ([_VP, _I, _I, _VP, ctypes.POINTER(_SZ)], _I),
+    "iso_neighbor_alltoallv_init": ([_VP, _VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
+                                     ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_allgatherv_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
+                                      ctypes.POINTER(_VP)], _I),
     "iso_start": ([_VP, _VP], _I),
     "iso_start_range": ([_VP, _I, _I, _VP], _I),
     "iso_request_set_graph": ([_VP, _I], _I),
@@ -283,6 +288,45 @@ def iso_neighbor_allgather_init(sendbuf, recvbuf, m, workspace, comm,
                                 algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
     return _init("iso_neighbor_allgather_init", sendbuf, recvbuf, m, workspace, workspace_bytes,
                  comm, algorithm)
+
+
+def _size_array(values):
+    return np.ascontiguousarray(values, dtype=np.uintp).reshape(-1)
+
+
+def iso_workspace_bytes_v(comm, op, algorithm, sizes):
+    out = ctypes.c_size_t()
+    arr = _size_array(sizes)
+    _check(load_library().iso_workspace_bytes_v(comm.handle, op, algorithm,
+                                                arr.ctypes.data if arr.size else None, ctypes.byref(out)),
+           "iso_workspace_bytes_v")
+    return out.value
+
+
+def iso_neighbor_alltoallv_init(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
+                                recv_displs, recv_extent, workspace, comm,
+                                algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    ss, sd, rs, rd = (_size_array(x) for x in (send_sizes, send_displs, recv_sizes, recv_displs))
+    h = ctypes.c_void_p()
+    p = lambda a: a.ctypes.data if a.size else None
+    st = load_library().iso_neighbor_alltoallv_init(
+        _ptr(sendbuf), p(ss), p(sd), send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
+    _check(st, "iso_neighbor_alltoallv_init")
+    return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def iso_neighbor_allgatherv_init(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs,
+                                 recv_extent, workspace, comm, algorithm=ISO_ALG_COMBINED,
+                                 workspace_bytes=None):
+    rs, rd = _size_array(recv_sizes), _size_array(recv_displs)
+    h = ctypes.c_void_p()
+    p = lambda a: a.ctypes.data if a.size else None
+    st = load_library().iso_neighbor_allgatherv_init(
+        _ptr(sendbuf), send_size, send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
+    _check(st, "iso_neighbor_allgatherv_init")
+    return Request(h.value, (sendbuf, recvbuf, workspace))
 
 
 def iso_start(req, stream=None):

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB_PATH = os.path.join(HERE, "libiso.so")
 SOURCES = [os.path.join(HERE, "csrc", "iso_api.hip"), os.path.join(HERE, "csrc", "iso_plan.cpp")]
-HEADERS = [os.path.join(HERE, "csrc", h) for h in ("iso_kernels.hpp", "iso_plan.hpp", "iso_fastdiv.hpp")]
+HEADERS = [os.path.join(HERE, "csrc", h) for h in ("iso_kernels.hpp", "iso_plan.hpp", "iso_fastdiv.hpp", "iso_bind.hpp")]
 HEADERS.append(os.path.join(ROOT, "include", "iso.h"))
 
 

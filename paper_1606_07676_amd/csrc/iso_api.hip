@@ -1,5 +1,6 @@
-// C ABI of libiso (see include/iso.h): handles, argument checks, binding of a
-// schedule to device buffers, and the per-round kernel launches.
+// C ABI of libiso (see include/iso.h): handles, argument checks and the launch
+// of a bound request's rounds.  The binding of a schedule to buffers lives in
+// iso_bind.hpp, the schedules in iso_plan.cpp, the kernels in iso_kernels.hpp.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -8,121 +9,13 @@
 #include <vector>
 
 #include "iso.h"
+#include "iso_bind.hpp"
 #include "iso_kernels.hpp"
 #include "iso_plan.hpp"
 
-namespace {
-
+namespace iso {
 thread_local int g_last_hip_error = 0;
-
-constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per launch
-
-#define ISO_HIP_TRY(expr)                              \
-    do {                                               \
-        hipError_t err_ = (expr);                      \
-        if (err_ != hipSuccess) {                      \
-            g_last_hip_error = (int)err_;              \
-            (void)hipGetLastError();                   \
-            return ISO_ERR_HIP;                        \
-        }                                              \
-    } while (0)
-
-struct Launch {
-    int kind;
-    uint32_t grid;
-    bool lds_table;
-    iso::ShiftArgs shift;
-    iso::VectorArgs vec;
-};
-
-struct Range {
-    uintptr_t lo;
-    size_t len;
-};
-
-bool overlap(const Range &a, const Range &b) {
-    if (!a.len || !b.len) return false;
-    return a.lo < b.lo + b.len && b.lo < a.lo + a.len;
 }
-
-// The range must lie inside one device allocation known to the HIP runtime.
-int check_device_range(const void *ptr, size_t len) {
-    if (!len) return ISO_SUCCESS;
-    if (!ptr) return ISO_ERR_ARG;
-    hipDeviceptr_t base = nullptr;
-    size_t size = 0;
-    hipError_t e = hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)ptr);
-    if (e != hipSuccess) {
-        g_last_hip_error = (int)e;
-        (void)hipGetLastError();
-        return ISO_ERR_POINTER;
-    }
-    const uintptr_t b = (uintptr_t)base, q = (uintptr_t)ptr;
-    if (q < b || q - b > size || len > size - (q - b)) return ISO_ERR_POINTER;
-    return ISO_SUCCESS;
-}
-
-int widest_vector(size_t m, std::initializer_list<const void *> ptrs) {
-    uintptr_t bits = (uintptr_t)m;
-    for (const void *p : ptrs) bits |= (uintptr_t)p;
-    int v = 16;
-    while (v > 1 && (bits & (uintptr_t)(v - 1))) v >>= 1;
-    return v;
-}
-
-void set_grid(Launch &l, uint32_t total, uint32_t k) {
-    const uint32_t n_tiles = (uint32_t)(((uint64_t)total + iso::kThreads - 1) / iso::kThreads);
-    // Runs of 128 tiles (512 KiB of units) per XCD: measured best over the five workloads
-    // (no runs: -5 % where the rank stride is a multiple of 4 KiB; runs of 512 tiles or more:
-    // -8 % and worse, the last incomplete span leaves XCDs idle).
-    uint32_t run_log2 = 7;
-    while (run_log2 > 0 && (8u << run_log2) > n_tiles) --run_log2;
-    const uint32_t span = 8u << run_log2;
-    l.grid = (uint32_t)((((uint64_t)n_tiles + span - 1) / span) * span);
-    iso::TileMap &tm = l.kind == ISO_ROUND_VECTOR ? l.vec.map : l.shift.map;
-    tm.n_tiles = n_tiles;
-    tm.run_log2 = run_log2;
-    l.lds_table = k <= iso::kLdsEntries;
-    if (l.kind == ISO_ROUND_VECTOR) {
-        l.vec.total = total;
-        l.vec.k = k;
-    } else {
-        l.shift.total = total;
-        l.shift.k = k;
-    }
-}
-
-template <typename V, bool LDS>
-void enqueue(const Launch &l, hipStream_t stream) {
-    if (l.kind == ISO_ROUND_VECTOR)
-        hipLaunchKernelGGL((iso::vector_round_kernel<V, LDS>), dim3(l.grid), dim3(iso::kThreads), 0,
-                           stream, l.vec);
-    else
-        hipLaunchKernelGGL((iso::shift_round_kernel<V, LDS>), dim3(l.grid), dim3(iso::kThreads), 0,
-                           stream, l.shift);
-}
-
-template <typename V>
-int launch_one(const Launch &l, hipStream_t stream) {
-    if (l.lds_table)
-        enqueue<V, true>(l, stream);
-    else
-        enqueue<V, false>(l, stream);
-    ISO_HIP_TRY(hipGetLastError());
-    return ISO_SUCCESS;
-}
-
-int launch_width(int vec, const Launch &l, hipStream_t stream) {
-    switch (vec) {
-        case 16: return launch_one<iso::vec16_t>(l, stream);
-        case 8:  return launch_one<iso::vec8_t>(l, stream);
-        case 4:  return launch_one<uint32_t>(l, stream);
-        case 2:  return launch_one<uint16_t>(l, stream);
-        default: return launch_one<uint8_t>(l, stream);
-    }
-}
-
-}  // namespace
 
 struct iso_comm_s {
     iso::Comm c;
@@ -134,10 +27,8 @@ struct iso_plan_s {
 };
 
 struct iso_request_s {
-    iso_plan_s plan;
-    iso_request_info_t info{};
-    void *dev_table = nullptr;
-    std::vector<Launch> launches;
+    iso::BoundRequest b;
+    iso_plan_s plan_view;                // what iso_request_plan hands out
     hipStream_t last_stream = nullptr;
     bool started = false;
     hipGraph_t graph = nullptr;          // the launches of one collective as a HIP graph
@@ -147,151 +38,7 @@ struct iso_request_s {
 
 namespace {
 
-size_t work_bytes(const iso::Plan &pl, size_t m) { return (size_t)pl.work_slots * (size_t)pl.comm.p * m; }
-
-int init_common(int op, const void *sendbuf, void *recvbuf, size_t m, void *workspace,
-                size_t workspace_bytes, iso_comm_t comm, int algorithm, iso_request_t *out) {
-    if (!out) return ISO_ERR_ARG;
-    *out = nullptr;
-    if (!comm) return ISO_ERR_ARG;
-    const iso::Comm &c = comm->c;
-    iso_request_s *rq = new iso_request_s();
-    struct Guard {
-        iso_request_s *r;
-        ~Guard() {
-            if (r) {
-                if (r->dev_table) (void)hipFree(r->dev_table);
-                delete r;
-            }
-        }
-    } guard{rq};
-
-    int st = iso::build_plan(c, op, algorithm, rq->plan.p);
-    if (st != ISO_SUCCESS) return st;
-    const iso::Plan &pl = rq->plan.p;
-    const uint64_t p = (uint64_t)c.p, s = (uint64_t)c.s;
-    if (m && p > (~(uint64_t)0 >> 1) / std::max<uint64_t>(1, s) / m) return ISO_ERR_TOO_LARGE;
-
-    iso_request_info_t &inf = rq->info;
-    inf.op = op; inf.algorithm = algorithm; inf.p = c.p; inf.s = c.s; inf.block_bytes = m;
-    inf.entries = pl.entries();
-    inf.bytes_read = inf.bytes_written = (uint64_t)inf.entries * p * m;
-    inf.delivered_bytes = p * s * m;
-    inf.workspace_bytes = work_bytes(pl, m);
-    inf.vector_bytes = 16;
-
-    const size_t send_len = (op == ISO_OP_ALLTOALL ? p * s : (s ? p : 0)) * m;
-    const size_t recv_len = p * s * m;
-    const size_t work_len = inf.workspace_bytes;
-    if (send_len && !sendbuf) return ISO_ERR_ARG;
-    if (recv_len && !recvbuf) return ISO_ERR_ARG;
-    if (work_len && !workspace) return ISO_ERR_WORKSPACE;
-    if (work_len > workspace_bytes) return ISO_ERR_WORKSPACE;
-    const Range rs{(uintptr_t)sendbuf, send_len}, rr{(uintptr_t)recvbuf, recv_len},
-        rw{(uintptr_t)workspace, work_len};
-    if (overlap(rs, rr) || overlap(rs, rw) || overlap(rr, rw)) return ISO_ERR_OVERLAP;
-
-    if (recv_len == 0) {          // m == 0, s == 0: nothing to move
-        inf.launches = 0;
-        guard.r = nullptr;
-        *out = rq;
-        return ISO_SUCCESS;
-    }
-    if ((st = check_device_range(sendbuf, send_len)) != ISO_SUCCESS) return st;
-    if ((st = check_device_range(recvbuf, recv_len)) != ISO_SUCCESS) return st;
-    if ((st = check_device_range(workspace, work_len)) != ISO_SUCCESS) return st;
-
-    const int vec = work_len ? widest_vector(m, {sendbuf, recvbuf, workspace})
-                             : widest_vector(m, {sendbuf, recvbuf});
-    inf.vector_bytes = vec;
-    const uint64_t chunks = m / (size_t)vec;
-    const uint64_t units_per_entry = p * chunks;
-    if (chunks > 0x7FFFFFFFu || units_per_entry > kMaxUnits) return ISO_ERR_TOO_LARGE;
-    const uint32_t k_max = (uint32_t)(kMaxUnits / units_per_entry);
-
-    // byte stride between ranks and base address per buffer kind
-    const uint64_t base[3] = {(uint64_t)(uintptr_t)sendbuf, (uint64_t)(uintptr_t)recvbuf,
-                              (uint64_t)(uintptr_t)workspace};
-    // send and recv: the caller's rank-major [p][s][m].  Workspace: slot-major [w][p][m], so
-    // that the blocks of one entry form a dense stream over the ranks whatever m is (rank-major
-    // workspace rows cost 20 % at m <= 64, where a row of w blocks is touched a few sectors at a time).
-    const uint64_t stride[3] = {op == ISO_OP_ALLTOALL ? s * m : m, s * m, m};
-    const uint64_t slot_step[3] = {m, m, p * m};
-
-    std::vector<iso::DevEntry> table;
-    table.reserve((size_t)inf.entries);
-    struct Pending { size_t first; Launch l; };
-    std::vector<Pending> pending;
-    for (const iso::Round &r : pl.rounds) {
-        size_t done = 0;
-        while (done < r.entries.size()) {
-            const uint32_t k = (uint32_t)std::min<size_t>(k_max, r.entries.size() - done);
-            Pending pd;
-            pd.first = table.size();
-            Launch &l = pd.l;
-            std::memset(&l, 0, sizeof(l));
-            l.kind = r.kind;
-            for (uint32_t q = 0; q < k; ++q) {
-                const iso_plan_entry_t &pe = r.entries[done + q];
-                iso::DevEntry de{};
-                de.src = base[pe.src_buf] + (uint64_t)pe.src_slot * slot_step[pe.src_buf];
-                de.dst = base[pe.dst_buf] + (uint64_t)pe.dst_slot * slot_step[pe.dst_buf];
-                de.src_stride = stride[pe.src_buf];
-                de.dst_stride = stride[pe.dst_buf];
-                de.shift = r.kind == ISO_ROUND_VECTOR ? (uint32_t)pe.neighbor : (uint32_t)pe.shift;
-                table.push_back(de);
-            }
-            const iso::FastDiv dch = iso::make_fastdiv((uint32_t)chunks), dk = iso::make_fastdiv(k);
-            if (r.kind == ISO_ROUND_VECTOR) {
-                l.vec.d = c.d;
-                l.vec.d_chunks = dch;
-                l.vec.d_k = dk;
-                for (int j = 0; j < c.d; ++j) {
-                    l.vec.d_dims[j] = iso::make_fastdiv((uint32_t)c.dims[j]);
-                    l.vec.inner[j] = (uint32_t)c.inner[j];
-                }
-            } else {
-                const bool shift = r.kind == ISO_ROUND_SHIFT;
-                l.shift.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
-                l.shift.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
-                l.shift.d_chunks = dch;
-                l.shift.d_k = dk;
-                l.shift.d_inner = iso::make_fastdiv(l.shift.inner);
-                l.shift.d_pj = iso::make_fastdiv(l.shift.pj);
-            }
-            set_grid(l, (uint32_t)(units_per_entry * k), k);
-            pending.push_back(pd);
-            done += k;
-        }
-    }
-
-    // one device table: the entries of all launches, then the [s][d] residues
-    const size_t entry_bytes = table.size() * sizeof(iso::DevEntry);
-    const size_t off_bytes = c.can.size() * sizeof(uint32_t);
-    if (entry_bytes + off_bytes) {
-        ISO_HIP_TRY(hipMalloc(&rq->dev_table, entry_bytes + off_bytes));
-        if (entry_bytes)
-            ISO_HIP_TRY(hipMemcpy(rq->dev_table, table.data(), entry_bytes, hipMemcpyHostToDevice));
-        if (off_bytes)
-            ISO_HIP_TRY(hipMemcpy((char *)rq->dev_table + entry_bytes, c.can.data(), off_bytes,
-                                  hipMemcpyHostToDevice));
-    }
-    const iso::DevEntry *dev_entries = (const iso::DevEntry *)rq->dev_table;
-    const uint32_t *dev_offsets = (const uint32_t *)((char *)rq->dev_table + entry_bytes);
-    for (Pending &pd : pending) {
-        if (pd.l.kind == ISO_ROUND_VECTOR) {
-            pd.l.vec.entries = dev_entries + pd.first;
-            pd.l.vec.offsets = dev_offsets;
-        } else {
-            pd.l.shift.entries = dev_entries + pd.first;
-        }
-        rq->launches.push_back(pd.l);
-    }
-    inf.launches = (int32_t)rq->launches.size();
-    guard.r = nullptr;
-    *out = rq;
-    return ISO_SUCCESS;
-}
+using iso::g_last_hip_error;
 
 template <typename F>
 int guarded(F &&f) {
@@ -302,6 +49,73 @@ int guarded(F &&f) {
     } catch (...) {
         return ISO_ERR_ARG;
     }
+}
+
+// Regular blocks: s blocks of m bytes back to back in neighbour order.
+iso::Layout regular_layout(const iso::Comm &c, int op, size_t m) {
+    iso::Layout lay;
+    const size_t s = (size_t)c.s;
+    lay.size.assign(s, m);
+    lay.send_displ.resize(s);
+    lay.recv_displ.resize(s);
+    for (size_t i = 0; i < s; ++i) {
+        lay.send_displ[i] = op == ISO_OP_ALLTOALL ? i * m : 0;
+        lay.recv_displ[i] = i * m;
+    }
+    lay.send_extent = lay.send_span = op == ISO_OP_ALLTOALL ? s * m : (s ? m : 0);
+    lay.recv_extent = lay.recv_span = s * m;
+    return lay;
+}
+
+// Blocks of a row must lie inside the row's extent; receive blocks must not overlap.
+int check_rows(const std::vector<uint64_t> &size, const std::vector<uint64_t> &displ, uint64_t extent,
+               bool disjoint, uint64_t &span) {
+    span = 0;
+    std::vector<std::pair<uint64_t, uint64_t>> iv;
+    for (size_t i = 0; i < size.size(); ++i) {
+        if (!size[i]) continue;
+        if (displ[i] > extent || size[i] > extent - displ[i]) return ISO_ERR_ARG;
+        span = std::max(span, displ[i] + size[i]);
+        iv.emplace_back(displ[i], displ[i] + size[i]);
+    }
+    if (disjoint) {
+        std::sort(iv.begin(), iv.end());
+        for (size_t q = 1; q < iv.size(); ++q)
+            if (iv[q].first < iv[q - 1].second) return ISO_ERR_OVERLAP;
+    }
+    return ISO_SUCCESS;
+}
+
+int make_request(int op, const iso::Layout &lay, const void *sendbuf, void *recvbuf, void *workspace,
+                 size_t workspace_bytes, iso_comm_t comm, int algorithm, iso_request_t *out) {
+    iso_request_s *rq = new iso_request_s();
+    struct Guard {
+        iso_request_s *r;
+        ~Guard() {
+            if (r) {
+                if (r->b.dev_table) (void)hipFree(r->b.dev_table);
+                delete r;
+            }
+        }
+    } guard{rq};
+    int st = iso::build_plan(comm->c, op, algorithm, rq->b.plan);
+    if (st != ISO_SUCCESS) return st;
+    st = iso::bind_request(rq->b, comm->c, lay, sendbuf, recvbuf, workspace, workspace_bytes);
+    if (st != ISO_SUCCESS) return st;
+    guard.r = nullptr;
+    *out = rq;
+    return ISO_SUCCESS;
+}
+
+int init_regular(int op, const void *sendbuf, void *recvbuf, size_t m, void *workspace,
+                 size_t workspace_bytes, iso_comm_t comm, int algorithm, iso_request_t *out) {
+    if (!out) return ISO_ERR_ARG;
+    *out = nullptr;
+    if (!comm) return ISO_ERR_ARG;
+    const uint64_t p = (uint64_t)comm->c.p, s = (uint64_t)comm->c.s;
+    if (m && p > (~(uint64_t)0 >> 2) / std::max<uint64_t>(1, s) / m) return ISO_ERR_TOO_LARGE;
+    return make_request(op, regular_layout(comm->c, op, m), sendbuf, recvbuf, workspace, workspace_bytes,
+                        comm, algorithm, out);
 }
 
 }  // namespace
@@ -412,7 +226,20 @@ int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t
         iso::Plan pl;
         int st = iso::build_plan(comm->c, op, algorithm, pl);
         if (st != ISO_SUCCESS) return st;
-        *bytes = work_bytes(pl, m);
+        *bytes = (size_t)iso::work_layout(pl, regular_layout(comm->c, op, m)).bytes;
+        return ISO_SUCCESS;
+    });
+}
+
+int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *sizes, size_t *bytes) {
+    return guarded([&]() -> int {
+        if (!comm || !bytes || (comm->c.s > 0 && !sizes)) return ISO_ERR_ARG;
+        iso::Plan pl;
+        int st = iso::build_plan(comm->c, op, algorithm, pl);
+        if (st != ISO_SUCCESS) return st;
+        iso::Layout lay;
+        lay.size.assign(sizes, sizes + comm->c.s);
+        *bytes = (size_t)iso::work_layout(pl, lay).bytes;
         return ISO_SUCCESS;
     });
 }
@@ -421,8 +248,8 @@ int iso_neighbor_alltoall_init(const void *sendbuf, void *recvbuf, size_t m, voi
                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                iso_request_t *req) {
     return guarded([&]() -> int {
-        return init_common(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
-                           algorithm, req);
+        return init_regular(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
+                            algorithm, req);
     });
 }
 
@@ -430,14 +257,68 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m, vo
                                 size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                 iso_request_t *req) {
     return guarded([&]() -> int {
-        return init_common(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
-                           algorithm, req);
+        return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
+                            algorithm, req);
+    });
+}
+
+int iso_neighbor_alltoallv_init(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                const size_t *recv_displs, size_t recv_extent, void *workspace,
+                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                iso_request_t *req) {
+    return guarded([&]() -> int {
+        if (!req) return ISO_ERR_ARG;
+        *req = nullptr;
+        if (!comm) return ISO_ERR_ARG;
+        const size_t s = (size_t)comm->c.s;
+        if (s && (!send_sizes || !send_displs || !recv_sizes || !recv_displs)) return ISO_ERR_ARG;
+        iso::Layout lay;
+        lay.size.assign(send_sizes, send_sizes + s);
+        lay.send_displ.assign(send_displs, send_displs + s);
+        lay.recv_displ.assign(recv_displs, recv_displs + s);
+        for (size_t i = 0; i < s; ++i)
+            if (send_sizes[i] != recv_sizes[i]) return ISO_ERR_ARG;      // sizes must match pairwise
+        lay.send_extent = send_extent;
+        lay.recv_extent = recv_extent;
+        int st;
+        if ((st = check_rows(lay.size, lay.send_displ, send_extent, false, lay.send_span)) != ISO_SUCCESS) return st;
+        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
+        return make_request(ISO_OP_ALLTOALL, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm,
+                            algorithm, req);
+    });
+}
+
+int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                 const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                 void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                 iso_request_t *req) {
+    return guarded([&]() -> int {
+        if (!req) return ISO_ERR_ARG;
+        *req = nullptr;
+        if (!comm) return ISO_ERR_ARG;
+        const size_t s = (size_t)comm->c.s;
+        if (s && (!recv_sizes || !recv_displs)) return ISO_ERR_ARG;
+        iso::Layout lay;
+        lay.size.assign(s, send_size);
+        lay.send_displ.assign(s, 0);
+        lay.recv_displ.assign(recv_displs, recv_displs + s);
+        for (size_t i = 0; i < s; ++i)
+            if (recv_sizes[i] != send_size) return ISO_ERR_ARG;         // every process sends one size
+        lay.send_extent = send_extent;
+        lay.recv_extent = recv_extent;
+        if (s && send_size > send_extent) return ISO_ERR_ARG;
+        lay.send_span = s ? send_size : 0;
+        int st;
+        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
+        return make_request(ISO_OP_ALLGATHER, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm,
+                            algorithm, req);
     });
 }
 
 int iso_request_set_graph(iso_request_t req, int enable) {
     if (!req) return ISO_ERR_ARG;
-    if (!enable || req->launches.empty()) {
+    if (!enable || req->b.launches.empty()) {
         req->use_graph = false;
         return ISO_SUCCESS;
     }
@@ -448,8 +329,8 @@ int iso_request_set_graph(iso_request_t req, int enable) {
         hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed);
         int st = ISO_SUCCESS;
         if (e == hipSuccess) {
-            for (const Launch &l : req->launches)
-                if ((st = launch_width(req->info.vector_bytes, l, cs)) != ISO_SUCCESS) break;
+            for (const iso::Launch &l : req->b.launches)
+                if ((st = iso::enqueue(req->b.info.vector_bytes, l, cs)) != ISO_SUCCESS) break;
             hipGraph_t g = nullptr;
             e = hipStreamEndCapture(cs, &g);
             if (e == hipSuccess && st == ISO_SUCCESS) {
@@ -479,13 +360,11 @@ int iso_start(iso_request_t req, void *hip_stream) {
     hipStream_t stream = (hipStream_t)hip_stream;
     if (req->use_graph) {
         ISO_HIP_TRY(hipGraphLaunch(req->graph_exec, stream));
-        req->last_stream = stream;
-        req->started = true;
-        return ISO_SUCCESS;
-    }
-    for (const Launch &l : req->launches) {
-        int st = launch_width(req->info.vector_bytes, l, stream);
-        if (st != ISO_SUCCESS) return st;
+    } else {
+        for (const iso::Launch &l : req->b.launches) {
+            int st = iso::enqueue(req->b.info.vector_bytes, l, stream);
+            if (st != ISO_SUCCESS) return st;
+        }
     }
     req->last_stream = stream;
     req->started = true;
@@ -493,11 +372,11 @@ int iso_start(iso_request_t req, void *hip_stream) {
 }
 
 int iso_start_range(iso_request_t req, int first, int count, void *hip_stream) {
-    if (!req || first < 0 || count < 0 || (size_t)first + (size_t)count > req->launches.size())
+    if (!req || first < 0 || count < 0 || (size_t)first + (size_t)count > req->b.launches.size())
         return ISO_ERR_ARG;
     hipStream_t stream = (hipStream_t)hip_stream;
     for (int q = first; q < first + count; ++q) {
-        int st = launch_width(req->info.vector_bytes, req->launches[(size_t)q], stream);
+        int st = iso::enqueue(req->b.info.vector_bytes, req->b.launches[(size_t)q], stream);
         if (st != ISO_SUCCESS) return st;
     }
     req->last_stream = stream;
@@ -507,21 +386,24 @@ int iso_start_range(iso_request_t req, int first, int count, void *hip_stream) {
 
 int iso_wait(iso_request_t req) {
     if (!req) return ISO_ERR_ARG;
-    if (!req->started || req->launches.empty()) return ISO_SUCCESS;
+    if (!req->started || req->b.launches.empty()) return ISO_SUCCESS;
     ISO_HIP_TRY(hipStreamSynchronize(req->last_stream));
     return ISO_SUCCESS;
 }
 
 int iso_request_info(iso_request_t req, iso_request_info_t *info) {
     if (!req || !info) return ISO_ERR_ARG;
-    *info = req->info;
+    *info = req->b.info;
     return ISO_SUCCESS;
 }
 
 int iso_request_plan(iso_request_t req, iso_plan_t *plan) {
-    if (!req || !plan) return ISO_ERR_ARG;
-    *plan = &req->plan;
-    return ISO_SUCCESS;
+    return guarded([&]() -> int {
+        if (!req || !plan) return ISO_ERR_ARG;
+        if (req->plan_view.p.rounds.empty()) req->plan_view.p = req->b.plan;
+        *plan = &req->plan_view;
+        return ISO_SUCCESS;
+    });
 }
 
 int iso_request_free(iso_request_t *req) {
@@ -530,8 +412,8 @@ int iso_request_free(iso_request_t *req) {
     if (*req) {
         if ((*req)->graph_exec) (void)hipGraphExecDestroy((*req)->graph_exec);
         if ((*req)->graph) (void)hipGraphDestroy((*req)->graph);
-        if ((*req)->dev_table) {
-            hipError_t e = hipFree((*req)->dev_table);
+        if ((*req)->b.dev_table) {
+            hipError_t e = hipFree((*req)->b.dev_table);
             if (e != hipSuccess) {
                 g_last_hip_error = (int)e;
                 (void)hipGetLastError();
@@ -548,7 +430,7 @@ const char *iso_error_string(int status) {
     switch (status) {
         case ISO_SUCCESS: return "success";
         case ISO_ERR_ARG: return "invalid argument";
-        case ISO_ERR_OVERLAP: return "send, receive and workspace buffers overlap";
+        case ISO_ERR_OVERLAP: return "buffers (or receive blocks) overlap";
         case ISO_ERR_WORKSPACE: return "workspace missing or too small";
         case ISO_ERR_HIP: return "HIP runtime error";
         case ISO_ERR_NOMEM: return "out of host memory";
@@ -563,30 +445,30 @@ int iso_last_hip_error(void) { return g_last_hip_error; }
 int iso_copy_reference(const void *src, void *dst, size_t bytes, void *hip_stream) {
     if (!bytes) return ISO_SUCCESS;
     if (!src || !dst) return ISO_ERR_ARG;
-    if (overlap(Range{(uintptr_t)src, bytes}, Range{(uintptr_t)dst, bytes})) return ISO_ERR_OVERLAP;
+    if (iso::overlap(iso::Range{(uintptr_t)src, bytes}, iso::Range{(uintptr_t)dst, bytes})) return ISO_ERR_OVERLAP;
     int st;
-    if ((st = check_device_range(src, bytes)) != ISO_SUCCESS) return st;
-    if ((st = check_device_range(dst, bytes)) != ISO_SUCCESS) return st;
+    if ((st = iso::check_device_range(src, bytes)) != ISO_SUCCESS) return st;
+    if ((st = iso::check_device_range(dst, bytes)) != ISO_SUCCESS) return st;
     hipStream_t stream = (hipStream_t)hip_stream;
-    const int vec = widest_vector(bytes, {src, dst});
-    const uint64_t units = bytes / (size_t)vec;
+    const uint32_t l2 = iso::unit_log2_of({(uint64_t)bytes, (uint64_t)(uintptr_t)src, (uint64_t)(uintptr_t)dst});
+    const uint64_t units = bytes >> l2;
     const uint64_t blocks = (units + iso::kThreads - 1) / iso::kThreads;
     if (blocks > 0x7FFFFFFFull) return ISO_ERR_TOO_LARGE;
     const dim3 grid((uint32_t)blocks), block(iso::kThreads);
-    switch (vec) {
-        case 16:
+    switch (l2) {
+        case 4:
             hipLaunchKernelGGL((iso::copy_kernel<iso::vec16_t>), grid, block, 0, stream,
                                (const iso::vec16_t *)src, (iso::vec16_t *)dst, units);
             break;
-        case 8:
+        case 3:
             hipLaunchKernelGGL((iso::copy_kernel<iso::vec8_t>), grid, block, 0, stream,
                                (const iso::vec8_t *)src, (iso::vec8_t *)dst, units);
             break;
-        case 4:
+        case 2:
             hipLaunchKernelGGL((iso::copy_kernel<uint32_t>), grid, block, 0, stream,
                                (const uint32_t *)src, (uint32_t *)dst, units);
             break;
-        case 2:
+        case 1:
             hipLaunchKernelGGL((iso::copy_kernel<uint16_t>), grid, block, 0, stream,
                                (const uint16_t *)src, (uint16_t *)dst, units);
             break;

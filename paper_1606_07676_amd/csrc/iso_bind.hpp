@@ -1,0 +1,386 @@
+// Binding of a schedule to device buffers: turns a plan plus a block layout
+// (sizes and displacements of the s blocks in a rank's send and receive rows)
+// into the device table of block index maps and the list of kernel launches.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <initializer_list>
+#include <numeric>
+#include <vector>
+
+#include "iso.h"
+#include "iso_kernels.hpp"
+#include "iso_plan.hpp"
+
+namespace iso {
+
+extern thread_local int g_last_hip_error;
+
+constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per launch
+
+#define ISO_HIP_TRY(expr)                              \
+    do {                                               \
+        hipError_t err_ = (expr);                      \
+        if (err_ != hipSuccess) {                      \
+            iso::g_last_hip_error = (int)err_;         \
+            (void)hipGetLastError();                   \
+            return ISO_ERR_HIP;                        \
+        }                                              \
+    } while (0)
+
+enum LaunchKernel { kShiftKernel = 0, kVectorKernel = 1, kBlockKernel = 2 };
+
+struct Launch {
+    int kernel;            // LaunchKernel
+    uint32_t grid;
+    bool lds_table;
+    ShiftArgs shift;
+    VectorArgs vec;
+    BlockArgs block;
+};
+
+// Sizes and displacements (bytes) of the s blocks inside one rank's send and
+// receive rows, and the distance between consecutive ranks' rows.
+struct Layout {
+    std::vector<uint64_t> size, send_displ, recv_displ;
+    uint64_t send_extent = 0, recv_extent = 0;
+    uint64_t send_span = 0, recv_span = 0;    // bytes of a row that blocks actually cover
+};
+
+struct Range {
+    uintptr_t lo;
+    size_t len;
+};
+
+inline bool overlap(const Range &a, const Range &b) {
+    if (!a.len || !b.len) return false;
+    return a.lo < b.lo + b.len && b.lo < a.lo + a.len;
+}
+
+// The range must lie inside one device allocation known to the HIP runtime.
+inline int check_device_range(const void *ptr, size_t len) {
+    if (!len) return ISO_SUCCESS;
+    if (!ptr) return ISO_ERR_ARG;
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    hipError_t e = hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)ptr);
+    if (e != hipSuccess) {
+        g_last_hip_error = (int)e;
+        (void)hipGetLastError();
+        return ISO_ERR_POINTER;
+    }
+    const uintptr_t b = (uintptr_t)base, q = (uintptr_t)ptr;
+    if (q < b || q - b > size || len > size - (q - b)) return ISO_ERR_POINTER;
+    return ISO_SUCCESS;
+}
+
+// log2 of the widest power-of-two unit (<= 16 bytes) that divides all the values
+inline uint32_t unit_log2_of(std::initializer_list<uint64_t> values) {
+    uint64_t bits = 0;
+    for (uint64_t v : values) bits |= v;
+    uint32_t l = 4;
+    while (l > 0 && (bits & ((uint64_t(1) << l) - 1))) --l;
+    return l;
+}
+
+inline uint64_t align16(uint64_t x) { return (x + 15) & ~uint64_t(15); }
+
+// Slot-major workspace: slot w holds one block per rank, p * size_w bytes, slots
+// back to back (each start rounded up to 16 bytes).  Dense streams per entry
+// whatever the block size is.
+struct WorkLayout {
+    std::vector<uint64_t> size, offset;
+    uint64_t bytes = 0;
+};
+
+inline WorkLayout work_layout(const Plan &pl, const Layout &lay) {
+    WorkLayout w;
+    w.size.assign((size_t)pl.work_slots, 0);
+    w.offset.assign((size_t)pl.work_slots, 0);
+    const uint64_t uniform = lay.size.empty() ? 0 : lay.size[0];
+    for (const Round &r : pl.rounds)
+        for (const iso_plan_entry_t &e : r.entries)
+            if (e.dst_buf == ISO_BUF_WORK) {
+                const uint64_t sz = (pl.op == ISO_OP_ALLTOALL && e.neighbor >= 0) ? lay.size[(size_t)e.neighbor]
+                                                                                  : uniform;
+                w.size[(size_t)e.dst_slot] = std::max(w.size[(size_t)e.dst_slot], sz);
+            }
+    for (int q = 0; q < pl.work_slots; ++q) {
+        w.offset[(size_t)q] = w.bytes;
+        w.bytes += align16((uint64_t)pl.comm.p * w.size[(size_t)q]);
+    }
+    return w;
+}
+
+inline void set_grid(Launch &l, uint32_t total, uint32_t k) {
+    const uint32_t n_tiles = (uint32_t)(((uint64_t)total + kThreads - 1) / kThreads);
+    // Runs of 128 tiles (512 KiB of units) per XCD: measured best over the five workloads
+    // (no runs: -5 % where the rank stride is a multiple of 4 KiB; runs of 512 tiles or more:
+    // -8 % and worse, the last incomplete span leaves XCDs idle).
+    uint32_t run_log2 = 7;
+    while (run_log2 > 0 && (8u << run_log2) > n_tiles) --run_log2;
+    const uint32_t span = 8u << run_log2;
+    l.grid = (uint32_t)((((uint64_t)n_tiles + span - 1) / span) * span);
+    TileMap &tm = l.kernel == kVectorKernel ? l.vec.map : l.kernel == kBlockKernel ? l.block.map : l.shift.map;
+    tm.n_tiles = n_tiles;
+    tm.run_log2 = run_log2;
+    l.lds_table = k <= kLdsEntries;
+    if (l.kernel == kVectorKernel) {
+        l.vec.total = total;
+        l.vec.k = k;
+    } else if (l.kernel == kBlockKernel) {
+        l.block.total = total;
+        l.block.k = k;
+    } else {
+        l.shift.total = total;
+        l.shift.k = k;
+    }
+}
+
+template <typename V, bool LDS>
+void enqueue_regular(const Launch &l, hipStream_t stream) {
+    if (l.kernel == kVectorKernel)
+        hipLaunchKernelGGL((vector_round_kernel<V, LDS>), dim3(l.grid), dim3(kThreads), 0, stream, l.vec);
+    else
+        hipLaunchKernelGGL((shift_round_kernel<V, LDS>), dim3(l.grid), dim3(kThreads), 0, stream, l.shift);
+}
+
+template <typename V>
+void enqueue_width(const Launch &l, hipStream_t stream) {
+    if (l.lds_table) enqueue_regular<V, true>(l, stream);
+    else enqueue_regular<V, false>(l, stream);
+}
+
+inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
+    if (l.kernel == kBlockKernel) {
+        if (l.lds_table)
+            hipLaunchKernelGGL((block_round_kernel<true>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
+        else
+            hipLaunchKernelGGL((block_round_kernel<false>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
+    } else {
+        switch (vector_bytes) {
+            case 16: enqueue_width<vec16_t>(l, stream); break;
+            case 8:  enqueue_width<vec8_t>(l, stream); break;
+            case 4:  enqueue_width<uint32_t>(l, stream); break;
+            case 2:  enqueue_width<uint16_t>(l, stream); break;
+            default: enqueue_width<uint8_t>(l, stream); break;
+        }
+    }
+    ISO_HIP_TRY(hipGetLastError());
+    return ISO_SUCCESS;
+}
+
+struct BoundRequest {
+    Plan plan;
+    iso_request_info_t info{};
+    void *dev_table = nullptr;
+    std::vector<Launch> launches;
+};
+
+// Checks the buffers, builds the device table and the launch list.  `rq.plan`
+// must already hold the schedule.
+inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, const void *sendbuf,
+                        void *recvbuf, void *workspace, size_t workspace_bytes) {
+    const Plan &pl = rq.plan;
+    const int op = pl.op;
+    const uint64_t p = (uint64_t)c.p;
+    const size_t s = (size_t)c.s;
+    iso_request_info_t &inf = rq.info;
+    inf.op = op; inf.algorithm = pl.algorithm; inf.p = c.p; inf.s = c.s;
+    inf.entries = pl.entries();
+    inf.vector_bytes = 16;
+    inf.block_bytes = 0;
+    inf.delivered_bytes = 0;
+    for (size_t i = 0; i < s; ++i) {
+        inf.block_bytes = std::max<uint64_t>(inf.block_bytes, lay.size[i]);
+        inf.delivered_bytes += p * lay.size[i];
+    }
+    const uint64_t limit = ~uint64_t(0) >> 2;
+    if (p && (lay.send_extent > limit / p || lay.recv_extent > limit / p)) return ISO_ERR_TOO_LARGE;
+
+    const WorkLayout wl = work_layout(pl, lay);
+    inf.workspace_bytes = wl.bytes;
+    auto entry_size = [&](const iso_plan_entry_t &e) -> uint64_t {
+        if (op == ISO_OP_ALLTOALL) return lay.size[(size_t)e.neighbor];
+        return s ? lay.size[0] : 0;
+    };
+    inf.bytes_read = 0;
+    for (const Round &r : pl.rounds)
+        for (const iso_plan_entry_t &e : r.entries) inf.bytes_read += p * entry_size(e);
+    inf.bytes_written = inf.bytes_read;
+
+    const size_t send_len = (inf.delivered_bytes && p) ? (size_t)((p - 1) * lay.send_extent + lay.send_span) : 0;
+    const size_t recv_len = (inf.delivered_bytes && p) ? (size_t)((p - 1) * lay.recv_extent + lay.recv_span) : 0;
+    const size_t work_len = inf.delivered_bytes ? (size_t)wl.bytes : 0;
+    if (send_len && !sendbuf) return ISO_ERR_ARG;
+    if (recv_len && !recvbuf) return ISO_ERR_ARG;
+    if (work_len && !workspace) return ISO_ERR_WORKSPACE;
+    if (work_len > workspace_bytes) return ISO_ERR_WORKSPACE;
+    const Range rs{(uintptr_t)sendbuf, send_len}, rr{(uintptr_t)recvbuf, recv_len},
+        rw{(uintptr_t)workspace, work_len};
+    if (overlap(rs, rr) || overlap(rs, rw) || overlap(rr, rw)) return ISO_ERR_OVERLAP;
+    if (inf.delivered_bytes == 0) {          // all blocks empty, or no neighbours: nothing to move
+        inf.launches = 0;
+        return ISO_SUCCESS;
+    }
+    int st;
+    if ((st = check_device_range(sendbuf, send_len)) != ISO_SUCCESS) return st;
+    if ((st = check_device_range(recvbuf, recv_len)) != ISO_SUCCESS) return st;
+    if ((st = check_device_range(workspace, work_len)) != ISO_SUCCESS) return st;
+
+    // address of rank 0's block and byte stride between ranks, per (buffer, slot)
+    auto place = [&](int buf, int slot, uint64_t &addr, uint64_t &stride) {
+        if (buf == ISO_BUF_SEND) {
+            addr = (uint64_t)(uintptr_t)sendbuf + (op == ISO_OP_ALLTOALL ? lay.send_displ[(size_t)slot] : lay.send_displ[0]);
+            stride = lay.send_extent;
+        } else if (buf == ISO_BUF_RECV) {
+            addr = (uint64_t)(uintptr_t)recvbuf + lay.recv_displ[(size_t)slot];
+            stride = lay.recv_extent;
+        } else {
+            addr = (uint64_t)(uintptr_t)workspace + wl.offset[(size_t)slot];
+            stride = wl.size[(size_t)slot];
+        }
+    };
+
+    // all entries, with their own unit width
+    struct HostEntry { DevEntry de; uint64_t size; };
+    std::vector<std::vector<HostEntry>> rounds(pl.rounds.size());
+    bool uniform = true;
+    uint64_t size0 = 0;
+    uint32_t min_log2 = 4;
+    bool first = true;
+    for (size_t ri = 0; ri < pl.rounds.size(); ++ri) {
+        const Round &r = pl.rounds[ri];
+        for (const iso_plan_entry_t &pe : r.entries) {
+            HostEntry he{};
+            he.size = entry_size(pe);
+            if (he.size == 0) continue;                       // empty blocks make no move
+            place(pe.src_buf, pe.src_slot, he.de.src, he.de.src_stride);
+            place(pe.dst_buf, pe.dst_slot, he.de.dst, he.de.dst_stride);
+            he.de.shift = r.kind == ISO_ROUND_VECTOR ? (uint32_t)pe.neighbor : (uint32_t)pe.shift;
+            he.de.unit_log2 = unit_log2_of({he.size, he.de.src, he.de.dst, he.de.src_stride, he.de.dst_stride});
+            const uint64_t units = he.size >> he.de.unit_log2;
+            if (units > 0x7FFFFFFFu) return ISO_ERR_TOO_LARGE;
+            he.de.units = (uint32_t)units;
+            if (first) { size0 = he.size; first = false; }
+            uniform = uniform && he.size == size0;
+            min_log2 = std::min(min_log2, he.de.unit_log2);
+            rounds[ri].push_back(he);
+        }
+    }
+    inf.vector_bytes = 1 << min_log2;
+
+    std::vector<DevEntry> table;
+    std::vector<uint32_t> prefixes;           // irregular launches: k+1 values each
+    struct Pending { size_t first_entry, first_prefix; Launch l; };
+    std::vector<Pending> pending;
+    for (size_t ri = 0; ri < pl.rounds.size(); ++ri) {
+        const Round &r = pl.rounds[ri];
+        const std::vector<HostEntry> &ents = rounds[ri];
+        size_t done = 0;
+        while (done < ents.size()) {
+            Pending pd{};
+            pd.first_entry = table.size();
+            pd.first_prefix = prefixes.size();
+            Launch &l = pd.l;
+            std::memset(&l, 0, sizeof(l));
+            uint32_t k = 0;
+            uint64_t total = 0;
+            if (uniform) {
+                // regular blocks: every entry has `chunks` units of the request's common width
+                const uint64_t chunks = size0 >> min_log2;
+                const uint64_t per_entry = p * chunks;
+                if (chunks > 0x7FFFFFFFu || per_entry > kMaxUnits) return ISO_ERR_TOO_LARGE;
+                k = (uint32_t)std::min<uint64_t>(kMaxUnits / per_entry, ents.size() - done);
+                total = per_entry * k;
+                l.kernel = r.kind == ISO_ROUND_VECTOR ? kVectorKernel : kShiftKernel;
+                const FastDiv dch = make_fastdiv((uint32_t)chunks), dk = make_fastdiv(k);
+                if (l.kernel == kVectorKernel) {
+                    l.vec.d = c.d;
+                    l.vec.d_chunks = dch;
+                    l.vec.d_k = dk;
+                    for (int j = 0; j < c.d; ++j) {
+                        l.vec.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
+                        l.vec.inner[j] = (uint32_t)c.inner[j];
+                    }
+                } else {
+                    const bool shift = r.kind == ISO_ROUND_SHIFT;
+                    l.shift.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
+                    l.shift.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
+                    l.shift.d_chunks = dch;
+                    l.shift.d_k = dk;
+                    l.shift.d_inner = make_fastdiv(l.shift.inner);
+                    l.shift.d_pj = make_fastdiv(l.shift.pj);
+                }
+                for (uint32_t q = 0; q < k; ++q) table.push_back(ents[done + q].de);
+            } else {
+                // irregular blocks: as many entries as fit the 32-bit unit index
+                l.kernel = kBlockKernel;
+                uint64_t row_units = 0;
+                prefixes.push_back(0);
+                while (done + k < ents.size()) {
+                    const uint64_t next = row_units + ents[done + k].de.units;
+                    if (next * p > kMaxUnits) break;
+                    row_units = next;
+                    table.push_back(ents[done + k].de);
+                    prefixes.push_back((uint32_t)row_units);
+                    ++k;
+                }
+                if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
+                total = row_units * p;
+                BlockArgs &b = l.block;
+                b.vector_round = r.kind == ISO_ROUND_VECTOR;
+                b.d_row = make_fastdiv((uint32_t)row_units);
+                const bool shift = r.kind == ISO_ROUND_SHIFT;
+                b.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
+                b.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
+                b.d_inner = make_fastdiv(b.inner);
+                b.d_pj = make_fastdiv(b.pj);
+                b.d = c.d;
+                for (int j = 0; j < c.d; ++j) {
+                    b.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
+                    b.inner_of[j] = (uint32_t)c.inner[j];
+                }
+            }
+            set_grid(l, (uint32_t)total, k);
+            pending.push_back(pd);
+            done += k;
+        }
+    }
+
+    // one device allocation: entries, then the [s][d] residues, then the prefix arrays
+    const size_t entry_bytes = table.size() * sizeof(DevEntry);
+    const size_t off_bytes = c.can.size() * sizeof(uint32_t);
+    const size_t pre_bytes = prefixes.size() * sizeof(uint32_t);
+    if (entry_bytes + off_bytes + pre_bytes) {
+        ISO_HIP_TRY(hipMalloc(&rq.dev_table, entry_bytes + off_bytes + pre_bytes));
+        char *d = (char *)rq.dev_table;
+        if (entry_bytes) ISO_HIP_TRY(hipMemcpy(d, table.data(), entry_bytes, hipMemcpyHostToDevice));
+        if (off_bytes) ISO_HIP_TRY(hipMemcpy(d + entry_bytes, c.can.data(), off_bytes, hipMemcpyHostToDevice));
+        if (pre_bytes)
+            ISO_HIP_TRY(hipMemcpy(d + entry_bytes + off_bytes, prefixes.data(), pre_bytes, hipMemcpyHostToDevice));
+    }
+    const DevEntry *dev_entries = (const DevEntry *)rq.dev_table;
+    const uint32_t *dev_offsets = (const uint32_t *)((char *)rq.dev_table + entry_bytes);
+    const uint32_t *dev_prefix = (const uint32_t *)((char *)rq.dev_table + entry_bytes + off_bytes);
+    for (Pending &pd : pending) {
+        if (pd.l.kernel == kVectorKernel) {
+            pd.l.vec.entries = dev_entries + pd.first_entry;
+            pd.l.vec.offsets = dev_offsets;
+        } else if (pd.l.kernel == kBlockKernel) {
+            pd.l.block.entries = dev_entries + pd.first_entry;
+            pd.l.block.prefix = dev_prefix + pd.first_prefix;
+            pd.l.block.offsets = dev_offsets;
+        } else {
+            pd.l.shift.entries = dev_entries + pd.first_entry;
+        }
+        rq.launches.push_back(pd.l);
+    }
+    inf.launches = (int32_t)rq.launches.size();
+    return ISO_SUCCESS;
+}
+
+}  // namespace iso

@@ -44,7 +44,9 @@ struct alignas(16) DevEntry {
     uint64_t src_stride;   // bytes between consecutive ranks in the source buffer
     uint64_t dst_stride;
     uint32_t shift;        // SHIFT rounds: residue v; VECTOR rounds: neighbour index
-    uint32_t pad[3];
+    uint32_t units;        // irregular launches: block size / unit width of this entry
+    uint32_t unit_log2;    // irregular launches: log2 of this entry's unit width in bytes
+    uint32_t pad;
 };
 
 // Workgroup -> tile mapping.  The hardware hands consecutive workgroup ids to
@@ -159,6 +161,83 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
     const V *sp = reinterpret_cast<const V *>(en.src + (uint64_t)srcR * en.src_stride) + ch;
     V *dp = reinterpret_cast<V *>(en.dst + (uint64_t)R * en.dst_stride) + ch;
     move_unit<V>(dp, sp);
+}
+
+// Irregular blocks (the v/w interfaces of Section 2): every entry has its own
+// block size and its own unit width (16 bytes where size and alignment allow,
+// narrower otherwise, e.g. a 1-byte corner block next to a 16 KiB face block).
+// A rank's units are the concatenation of its entries' units; `prefix[e]` is
+// the first unit of entry e.  The flat index is split into (rank, unit in row),
+// the entry is found by binary search in the prefix array.
+struct BlockArgs {
+    const DevEntry *entries;
+    const uint32_t *prefix;    // [k + 1]
+    const uint32_t *offsets;   // [s][d] residues (VECTOR rounds)
+    TileMap map;
+    uint32_t total;            // p * row_units
+    uint32_t k;
+    uint32_t vector_round;     // 0: shift along one dimension, 1: full offset vector
+    uint32_t inner, pj;        // shift rounds
+    int32_t d;                 // vector rounds
+    FastDiv d_row, d_inner, d_pj;
+    FastDiv d_dims[ISO_MAX_DIMS];
+    uint32_t inner_of[ISO_MAX_DIMS];
+};
+
+template <typename V>
+__device__ __forceinline__ void move_at(uint64_t dst, uint64_t src, uint32_t ch) {
+    move_unit<V>(reinterpret_cast<V *>(dst) + ch, reinterpret_cast<const V *>(src) + ch);
+}
+
+template <bool LDS>
+__global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
+    __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
+    __shared__ uint32_t lds_prefix[LDS ? kLdsEntries + 1 : 1];
+    const uint32_t *prefix = a.prefix;
+    if constexpr (LDS) {
+        if (threadIdx.x <= a.k) lds_prefix[threadIdx.x] = a.prefix[threadIdx.x];
+        prefix = lds_prefix;
+    }
+    const EntryTable<LDS> table(a.entries, a.k, lds);     // synchronises the workgroup when LDS
+    uint32_t tile;
+    if (!tile_of_block(a.map, tile)) return;
+    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
+    if (u >= a.total) return;
+    uint32_t R, w;
+    fast_divmod(u, a.d_row, R, w);
+    uint32_t lo = 0, hi = a.k;                 // largest e with prefix[e] <= w
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (prefix[mid] <= w) lo = mid;
+        else hi = mid;
+    }
+    const DevEntry en = table[lo];
+    const uint32_t ch = w - prefix[lo];
+    int64_t srcR = R;
+    if (a.vector_round) {
+        const uint32_t *c = a.offsets + (size_t)en.shift * a.d;
+        uint32_t rem = R;
+        for (int j = a.d - 1; j >= 0; --j) {
+            uint32_t q, rj;
+            fast_divmod(rem, a.d_dims[j], q, rj);
+            rem = q;
+            const uint32_t cj = c[j];
+            srcR += (rj >= cj ? -(int64_t)cj : (int64_t)(a.d_dims[j].div - cj)) * (int64_t)a.inner_of[j];
+        }
+    } else {
+        const uint32_t q = fast_div(R, a.d_inner);
+        const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
+        srcR += (rj >= en.shift ? -(int64_t)en.shift : (int64_t)(a.pj - en.shift)) * (int64_t)a.inner;
+    }
+    const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
+    const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
+    switch (en.unit_log2) {
+        case 4: move_at<vec16_t>(dst, src, ch); break;
+        case 3: move_at<vec8_t>(dst, src, ch); break;
+        case 2: move_at<uint32_t>(dst, src, ch); break;
+        case 1: move_at<uint16_t>(dst, src, ch); break;
+        default: move_at<uint8_t>(dst, src, ch); break;
+    }
 }
 
 // Plain streaming copy with the same access shape: the measured ceiling.

@@ -1,0 +1,171 @@
+"""GPU parity of the irregular (v/w) collectives against the CPU oracle, bit for
+bit: per-neighbour block sizes and displacements, mixed unit widths, empty
+blocks, bytes between blocks left untouched."""
+import numpy as np
+import pytest
+import torch
+
+import iso_inputs as gen
+import paper_1606_07676_amd as iso
+from oracle import iso_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
+        iso.ISO_ALG_ONEHOP]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop"}
+RNG = np.random.default_rng(77)
+
+CASES = [
+    ((4, 3, 5), gen.moore(3, 1)),
+    ((6, 5), gen.von_neumann(2, 2)),
+    ((9, 9, 9), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0), (3, 3, 2),
+                 (4, 0, 1), (4, 0, 2), (4, 1, 1)]),
+    ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),
+    ((37, 11), gen.moore(2, 2)),
+]
+
+
+def _comm(dims, offsets):
+    return iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(len(offsets), len(dims)))
+
+
+def _layouts(s, flavour):
+    """(sizes, send_displs, send_extent, recv_displs, recv_extent)"""
+    if flavour == "stencil16":          # 16-byte friendly, mixed big and tiny
+        sizes = [(4096, 64, 16, 1)[i % 4] for i in range(s)]
+        sd, sext = gen.packed_displacements(sizes, 16)
+        rd, rext = gen.packed_displacements(sizes[::-1], 16)
+        rd = rd[::-1]
+    elif flavour == "odd":              # odd sizes, byte-aligned, gaps, an empty block
+        sizes = [int(x) for x in RNG.integers(1, 40, size=s)]
+        sizes[s // 2] = 0
+        sd, sext = gen.packed_displacements(sizes, 1)
+        sext += 3
+        rd, at = [0] * s, 7
+        for i in reversed(range(s)):
+            rd[i] = at
+            at += sizes[i] + int(RNG.integers(0, 5))
+        rext = at + 5
+    else:                               # equal sizes, scattered displacements: regular kernel path
+        sizes = [48] * s
+        sd = [64 * i + 16 for i in range(s)]
+        sext = 64 * s + 32
+        rd = [80 * (s - 1 - i) for i in range(s)]
+        rext = 80 * s
+    return sizes, sd, sext, rd, rext
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("flavour", ["stencil16", "odd", "equal"])
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_alltoallv_every_byte(case, flavour, alg):
+    dims, offsets = CASES[case]
+    p, s = int(np.prod(dims)), len(offsets)
+    sizes, sd, sext, rd, rext = _layouts(s, flavour)
+    send_h = RNG.integers(0, 256, size=(p, sext), dtype=np.uint8)
+    want = orc.alltoallv(dims, offsets, send_h, sizes, sd, np.full((p, rext), 0xEE, np.uint8), rd)
+    comm = _comm(dims, offsets)
+    send = torch.from_numpy(send_h).to(DEV)
+    recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+    wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+    work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm, alg)
+    info = iso.iso_request_info(req)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} {flavour} alg={alg}"
+    assert np.array_equal(send.cpu().numpy(), send_h)
+    assert info["delivered_bytes"] == p * sum(sizes)
+    if flavour == "stencil16":
+        assert info["vector_bytes"] == 1          # narrowest unit in the request: the 1-byte blocks
+    iso.iso_request_free(req)
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("case", range(len(CASES)))
+def test_allgatherv_every_byte(case, alg):
+    dims, offsets = CASES[case]
+    p, s = int(np.prod(dims)), len(offsets)
+    for m, sext, gap in ((48, 64, 16), (7, 7, 2), (1024, 1024, 0)):
+        rd = [5 * (gap > 0 and m % 16 != 0) + i * (m + gap) for i in range(s)]
+        rext = rd[-1] + m + 3 if s else 8
+        send_h = RNG.integers(0, 256, size=(p, sext), dtype=np.uint8)
+        want = orc.allgatherv(dims, offsets, send_h, m, np.full((p, rext), 0xEE, np.uint8), rd)
+        comm = _comm(dims, offsets)
+        send = torch.from_numpy(send_h).to(DEV)
+        recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, alg, [m] * s)
+        work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_allgatherv_init(send, m, sext, recv, [m] * s, rd, rext, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} m={m} alg={alg}"
+        iso.iso_request_free(req)
+
+
+def test_irregular_argument_checks():
+    dims, offsets = (4, 4), gen.moore(2, 1)
+    comm = _comm(dims, offsets)
+    s = 8
+    sizes = [16] * s
+    d, ext = gen.packed_displacements(sizes, 16)
+    buf = torch.zeros(16 * ext, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(16 * ext, dtype=torch.uint8, device=DEV)
+    work = torch.zeros(1 << 16, dtype=torch.uint8, device=DEV)
+    bad = list(sizes)
+    bad[3] = 32
+    with pytest.raises(iso.IsoError) as e:                     # sizes differ pairwise
+        iso.iso_neighbor_alltoallv_init(buf, sizes, d, ext, out, bad, d, ext, work, comm)
+    assert e.value.status == iso.ISO_ERR_ARG
+    with pytest.raises(iso.IsoError) as e:                     # a block sticks out of its row
+        iso.iso_neighbor_alltoallv_init(buf, sizes, d, ext - 8, out, sizes, d, ext, work, comm)
+    assert e.value.status == iso.ISO_ERR_ARG
+    clash = list(d)
+    clash[5] = d[4] + 8
+    with pytest.raises(iso.IsoError) as e:                     # receive blocks overlap
+        iso.iso_neighbor_alltoallv_init(buf, sizes, d, ext, out, sizes, clash, ext, work, comm)
+    assert e.value.status == iso.ISO_ERR_OVERLAP
+    req = iso.iso_neighbor_alltoallv_init(buf, sizes, clash, ext, out, sizes, d, ext, work, comm)  # send may
+    iso.iso_request_free(req)
+    with pytest.raises(iso.IsoError) as e:                     # allgather: one size for all
+        iso.iso_neighbor_allgatherv_init(buf, 16, 16, out, bad, d, ext, work, comm)
+    assert e.value.status == iso.ISO_ERR_ARG
+    req = iso.iso_neighbor_alltoallv_init(buf, [0] * s, d, ext, out, [0] * s, d, ext, None, comm)
+    assert iso.iso_request_info(req)["launches"] == 0
+    iso.iso_start(req)
+    iso.iso_wait(req)
+
+
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_SX_FUSED], ids=lambda a: ALG_NAMES[a])
+def test_stencil_sized_alltoallv_at_scale(alg):
+    """The paper's irregular experiment shape (Section 4): Moore d=3 r=1, block of
+    neighbour i has base^(3 - ||C^i||_1) bytes; base 128 on a 16^3 torus (400 MB
+    per buffer).  Every block compared with what the oracle's source rank sent."""
+    dims, offsets, base, seed = (16, 16, 16), gen.moore(3, 1), 128, 4242
+    p, s = 4096, 26
+    sizes = gen.stencil_block_sizes(offsets, base)
+    sd, sext = gen.packed_displacements(sizes, 16)
+    rd, rext = sd, sext
+    comm = _comm(dims, offsets)
+    ranks = torch.arange(p, device=DEV)
+    send = torch.zeros((p, sext), dtype=torch.uint8, device=DEV)
+    for i in range(s):
+        send[:, sd[i]:sd[i] + sizes[i]] = gen.block_bytes_torch(seed, ranks, torch.full_like(ranks, i), sizes[i])
+    recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+    wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+    work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm, alg)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    src = torch.from_numpy(orc.source_ranks(dims, offsets)).to(DEV)
+    covered = torch.zeros(rext, dtype=torch.bool, device=DEV)
+    for i in range(s):
+        want = gen.block_bytes_torch(seed, src[:, i], torch.full_like(ranks, i), sizes[i])
+        assert torch.equal(recv[:, rd[i]:rd[i] + sizes[i]], want), f"block {i}"
+        covered[rd[i]:rd[i] + sizes[i]] = True
+    assert bool((recv[:, ~covered] == 0xEE).all())
+    info = iso.iso_request_info(req)
+    assert info["delivered_bytes"] == p * sum(sizes)
+    iso.iso_request_free(req)

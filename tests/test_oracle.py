@@ -346,3 +346,49 @@ def test_onehop_figure1_counts(golden):
     assert sum(len(p) for _, p in trace) == int(golden["fig1_onehop_V"])
     _, moves = orc.replay_onehop_allgather(dims, offs, send[:, 0], return_moves=True)
     assert moves == int(golden["fig1_onehop_W"])
+
+
+# ---------------------------------------------------------------- irregular variants
+
+def test_irregular_reduces_to_regular_and_to_roll(golden):
+    dims, offsets = (4, 3, 5), gen.moore(3, 1)
+    p, s, m = 60, 26, 8
+    send = _rand_send(p, s, m)
+    displs = [i * m for i in range(s)]
+    recv = np.zeros((p, s * m), np.uint8)
+    orc.alltoallv(dims, offsets, send.reshape(p, s * m), [m] * s, displs, recv, displs)
+    assert np.array_equal(recv.reshape(p, s, m), orc.alltoall(dims, offsets, send))
+    # genuinely irregular: stencil sizes, padded displacements on the send side, reversed order on the
+    # receive side; every block checked against numpy.roll, every other byte must keep its value
+    sizes = gen.stencil_block_sizes(offsets, 3)
+    sd, sext = gen.packed_displacements(sizes, 4)
+    order = list(range(s))[::-1]
+    rd, at = [0] * s, 5
+    for i in order:
+        rd[i] = at
+        at += sizes[i] + 2
+    rext = at + 3
+    send_rows = RNG.integers(0, 256, size=(p, sext), dtype=np.uint8)
+    recv_rows = np.full((p, rext), 0xEE, np.uint8)
+    orc.alltoallv(dims, offsets, send_rows, sizes, sd, recv_rows, rd)
+    covered = np.zeros(rext, bool)
+    for i, C in enumerate(offsets):
+        blk = send_rows[:, sd[i]:sd[i] + sizes[i]].reshape(dims + (sizes[i],))
+        want = np.roll(blk, C, axis=(0, 1, 2)).reshape(p, sizes[i])
+        assert np.array_equal(recv_rows[:, rd[i]:rd[i] + sizes[i]], want)
+        covered[rd[i]:rd[i] + sizes[i]] = True
+    assert (recv_rows[:, ~covered] == 0xEE).all()
+    # allgather with displacements
+    one = RNG.integers(0, 256, size=(p, 7), dtype=np.uint8)
+    rows = np.full((p, rext), 0xEE, np.uint8)
+    gd = [3 + 9 * i for i in range(s)]
+    rows = np.full((p, 3 + 9 * s), 0xEE, np.uint8)
+    orc.allgatherv(dims, offsets, one, 7, rows, gd)
+    ref = orc.allgather(dims, offsets, one)
+    for i in range(s):
+        assert np.array_equal(rows[:, gd[i]:gd[i] + 7], ref[:, i])
+    # the paper's worked sizes for base 512 in three dimensions
+    big = gen.stencil_block_sizes(offsets, 512)
+    assert sorted(set(big)) == _ints(golden["irregular_d3_base512_sizes"])
+    assert abs(sum(big) / 1e6 - float(golden["irregular_d3_base512_total_MB"])) < 0.1
+    assert (big.count(262144), big.count(512), big.count(1)) == (6, 12, 8)
