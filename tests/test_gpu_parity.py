@@ -281,6 +281,27 @@ def test_named_workloads_full_size(key, alg):
         _check_full(cfg, _ops(cfg)[0], alg, cfg.m, seed=77 + key, host_oracle=False)
 
 
+def test_round_is_split_when_the_unit_index_would_overflow():
+    """Byte-wide units (receive buffer misaligned by one byte) and 16 KiB blocks on the
+    32^3 torus: one round of 9 entries has 9 * 2^29 units, more than a launch's 32-bit
+    unit index holds, so the binding must split rounds over several launches."""
+    dims, offsets, m, seed = (32, 32, 32), gen.moore(3, 1), 16384, 31
+    p, s = 32768, 26
+    send = gen.alltoall_send_torch(seed, p, s, m, device=DEV)
+    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m, send, misalign=1)
+    assert info["vector_bytes"] == 1
+    assert info["launches"] == 12               # 6 rounds, each 7 + 2 entries
+    src = orc.source_ranks(dims, offsets)
+    slots = torch.arange(s, device=DEV)[None, :]
+    chunk = (256 << 20) // (s * m)
+    for lo in range(0, p, chunk):
+        hi = min(p, lo + chunk)
+        want = gen.block_bytes_torch(seed, torch.from_numpy(src[lo:hi]).to(DEV), slots, m)
+        assert torch.equal(recv[lo:hi], want), f"ranks {lo}:{hi}"
+    del send, recv
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
 def test_config5_full_size(alg):
     cfg = gen.get_config(5)
