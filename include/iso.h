@@ -122,6 +122,11 @@ typedef struct {
     int32_t neighbor;            /* index i of the offset whose route this move belongs to
                                     (allgather temporaries: -1); VECTOR rounds: source is
                                     R (-) C^neighbor                                        */
+    int32_t ref;                 /* a neighbour whose route passes through this move (always
+                                    valid; equals `neighbor` when that is >= 0).  On a mesh
+                                    the move happens at rank R only if R minus C^ref, taken
+                                    over the dimensions routed so far, is inside the mesh    */
+    int32_t reserved;
 } iso_plan_entry_t;
 
 typedef struct {
@@ -146,6 +151,17 @@ typedef struct {
  * the send and receive buffers.  Purely local host computation, O(s d). */
 int iso_neighborhood_create(int d, const int32_t *dims, int s,
                             const int32_t *rel_coords, iso_comm_t *comm);
+/* Same, on a mesh (Section 7: non-periodic dimensions, as in an MPI Cartesian
+ * topology).  periodic: host, d flags (non-zero = the dimension wraps); NULL =
+ * all periodic = iso_neighborhood_create.  In a non-periodic dimension
+ * coordinates are taken as given (not reduced) and nothing wraps: a rank whose
+ * source R - C^i lies outside the mesh receives nothing for neighbour i and its
+ * i-th receive block keeps its content.  Intermediate hops of the all-to-all
+ * then alternate between two workspace slots instead of using the receive
+ * buffer, so that blocks in transit never overwrite a block that stays
+ * untouched.  ISO_ALG_ONEHOP is not available on a mesh (ISO_ERR_ARG). */
+int iso_neighborhood_create_mesh(int d, const int32_t *dims, const int32_t *periodic, int s,
+                                 const int32_t *rel_coords, iso_comm_t *comm);
 int iso_neighborhood_info(iso_comm_t comm, iso_comm_info_t *info);
 /* Frees the handle and sets *comm = NULL.  Plans and requests made from it
  * keep their own copy of what they need and stay valid. */

@@ -392,3 +392,44 @@ def allgatherv(dims, offsets, send_rows, size, recv_rows, recv_displs):
     for i in range(len(offsets)):
         recv_rows[:, recv_displs[i]:recv_displs[i] + size] = send_rows[src[:, i], :size]
     return recv_rows
+
+
+# ---------------------------------------------------------------------------
+# Part 5: meshes (Section 7: dimensions may be non-periodic, as in an MPI
+# Cartesian topology).  In a non-periodic dimension nothing wraps: a process
+# whose source R - C^i would lie outside the mesh receives nothing for
+# neighbour i and its i-th receive block keeps its content.
+# ---------------------------------------------------------------------------
+
+def source_ranks_mesh(dims, periodic, offsets, ranks=None):
+    """(src, valid): int64 (n, s) source ranks and bool (n, s) "a source exists".
+    Periodic dimensions wrap as on the torus; in the others R - C^i must stay in
+    [0, p_j), using the coordinate as given (no reduction)."""
+    dims_a = np.asarray(dims, dtype=np.int64)
+    per = np.asarray(periodic, dtype=bool)
+    p = int(np.prod(dims_a))
+    ranks = np.arange(p, dtype=np.int64) if ranks is None else np.asarray(ranks, np.int64)
+    offs = np.asarray(offsets, dtype=np.int64).reshape(-1, len(dims))
+    raw = rank_to_coords(ranks, dims)[:, None, :] - offs[None, :, :]          # (n, s, d)
+    inside = (raw >= 0) & (raw < dims_a)
+    valid = np.all(inside | per, axis=2)
+    src = coords_to_rank(np.where(per, np.mod(raw, dims_a), np.clip(raw, 0, dims_a - 1)), dims)
+    return src, valid
+
+
+def alltoall_mesh(dims, periodic, offsets, send, recv):
+    """recv[R][i] = send[R - C^i][i] where that source exists; other blocks of
+    `recv` (modified in place, returned) keep their content."""
+    src, valid = source_ranks_mesh(dims, periodic, offsets)
+    for i in range(len(offsets)):
+        v = valid[:, i]
+        recv[v, i] = send[src[v, i], i]
+    return recv
+
+
+def allgather_mesh(dims, periodic, offsets, send, recv):
+    src, valid = source_ranks_mesh(dims, periodic, offsets)
+    for i in range(len(offsets)):
+        v = valid[:, i]
+        recv[v, i] = send[src[v, i]]
+    return recv

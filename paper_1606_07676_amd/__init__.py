@@ -13,7 +13,7 @@ from .binding import (  # noqa: F401
     ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP,
     ISO_ERR_NOMEM, ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_MAX_DIMS,
     Comm, Plan, Request,
-    iso_neighborhood_create, iso_neighborhood_info, iso_neighborhood_free,
+    iso_neighborhood_create, iso_neighborhood_create_mesh, iso_neighborhood_info, iso_neighborhood_free,
     iso_plan_create, iso_plan_info, iso_plan_round, iso_plan_entries, iso_plan_free,
     iso_workspace_bytes, iso_neighbor_alltoall_init, iso_neighbor_allgather_init,
     iso_workspace_bytes_v, iso_neighbor_alltoallv_init, iso_neighbor_allgatherv_init,

@@ -52,7 +52,8 @@ class iso_round_info_t(ctypes.Structure):
 class iso_plan_entry_t(ctypes.Structure):
     _fields_ = [("src_buf", ctypes.c_int32), ("src_slot", ctypes.c_int32),
                 ("dst_buf", ctypes.c_int32), ("dst_slot", ctypes.c_int32),
-                ("shift", ctypes.c_int32), ("neighbor", ctypes.c_int32)]
+                ("shift", ctypes.c_int32), ("neighbor", ctypes.c_int32),
+                ("ref", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class iso_request_info_t(ctypes.Structure):
@@ -79,6 +80,7 @@ def library_path():
 _VP, _I, _SZ = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
 _PROTOTYPES = {
     "iso_neighborhood_create": ([_I, _VP, _I, _VP, ctypes.POINTER(_VP)], _I),
+    "iso_neighborhood_create_mesh": ([_I, _VP, _VP, _I, _VP, ctypes.POINTER(_VP)], _I),
     "iso_neighborhood_info": ([_VP, ctypes.POINTER(iso_comm_info_t)], _I),
     "iso_neighborhood_free": ([ctypes.POINTER(_VP)], _I),
     "iso_plan_create": ([_VP, _I, _I, ctypes.POINTER(_VP)], _I),
@@ -220,6 +222,21 @@ def iso_neighborhood_create(dims, rel_coords):
                                                 rel.ctypes.data if rel.size else None,
                                                 ctypes.byref(h))
     _check(st, "iso_neighborhood_create")
+    return Comm(h.value)
+
+
+def iso_neighborhood_create_mesh(dims, periodic, rel_coords):
+    """As iso_neighborhood_create; periodic: d flags (False = that dimension does not wrap)."""
+    dims_a = np.ascontiguousarray(dims, dtype=np.int32).reshape(-1)
+    d = dims_a.size
+    per = np.ascontiguousarray([1 if x else 0 for x in periodic], dtype=np.int32)
+    rel = np.ascontiguousarray(rel_coords, dtype=np.int32).reshape(-1)
+    if d == 0 or per.size != d or rel.size % d:
+        raise ValueError("need d periodic flags and s*d relative coordinates")
+    h = ctypes.c_void_p()
+    st = load_library().iso_neighborhood_create_mesh(d, dims_a.ctypes.data, per.ctypes.data, rel.size // d,
+                                                     rel.ctypes.data if rel.size else None, ctypes.byref(h))
+    _check(st, "iso_neighborhood_create_mesh")
     return Comm(h.value)
 
 

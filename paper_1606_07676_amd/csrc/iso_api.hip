@@ -124,11 +124,16 @@ extern "C" {
 
 int iso_neighborhood_create(int d, const int32_t *dims, int s, const int32_t *rel_coords,
                             iso_comm_t *comm) {
+    return iso_neighborhood_create_mesh(d, dims, nullptr, s, rel_coords, comm);
+}
+
+int iso_neighborhood_create_mesh(int d, const int32_t *dims, const int32_t *periodic, int s,
+                                 const int32_t *rel_coords, iso_comm_t *comm) {
     return guarded([&]() -> int {
         if (!comm) return ISO_ERR_ARG;
         *comm = nullptr;
         iso_comm_s *h = new iso_comm_s();
-        int st = iso::build_comm(d, dims, s, rel_coords, h->c);
+        int st = iso::build_comm(d, dims, periodic, s, rel_coords, h->c);
         if (st != ISO_SUCCESS) {
             delete h;
             return st;

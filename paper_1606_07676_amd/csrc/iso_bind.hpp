@@ -37,6 +37,7 @@ struct Launch {
     int kernel;            // LaunchKernel
     uint32_t grid;
     bool lds_table;
+    bool mesh;
     ShiftArgs shift;
     VectorArgs vec;
     BlockArgs block;
@@ -156,10 +157,14 @@ void enqueue_width(const Launch &l, hipStream_t stream) {
 
 inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
     if (l.kernel == kBlockKernel) {
-        if (l.lds_table)
-            hipLaunchKernelGGL((block_round_kernel<true>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
-        else
-            hipLaunchKernelGGL((block_round_kernel<false>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
+        const dim3 grid(l.grid), block(kThreads);
+        if (l.mesh) {
+            if (l.lds_table) hipLaunchKernelGGL((block_round_kernel<true, true>), grid, block, 0, stream, l.block);
+            else hipLaunchKernelGGL((block_round_kernel<false, true>), grid, block, 0, stream, l.block);
+        } else {
+            if (l.lds_table) hipLaunchKernelGGL((block_round_kernel<true, false>), grid, block, 0, stream, l.block);
+            else hipLaunchKernelGGL((block_round_kernel<false, false>), grid, block, 0, stream, l.block);
+        }
     } else {
         switch (vector_bytes) {
             case 16: enqueue_width<vec16_t>(l, stream); break;
@@ -261,13 +266,23 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             place(pe.src_buf, pe.src_slot, he.de.src, he.de.src_stride);
             place(pe.dst_buf, pe.dst_slot, he.de.dst, he.de.dst_stride);
             he.de.shift = r.kind == ISO_ROUND_VECTOR ? (uint32_t)pe.neighbor : (uint32_t)pe.shift;
-            he.de.unit_log2 = unit_log2_of({he.size, he.de.src, he.de.dst, he.de.src_stride, he.de.dst_stride});
-            const uint64_t units = he.size >> he.de.unit_log2;
+            const uint32_t l2 = unit_log2_of({he.size, he.de.src, he.de.dst, he.de.src_stride, he.de.dst_stride});
+            const uint64_t units = he.size >> l2;
             if (units > 0x7FFFFFFFu) return ISO_ERR_TOO_LARGE;
             he.de.units = (uint32_t)units;
+            he.de.ref = (uint32_t)pe.ref;
+            // mesh: the non-periodic dimensions routed so far in which C^ref is non-zero
+            uint32_t mask = 0;
+            if (c.mesh && r.kind != ISO_ROUND_SELF)
+                for (int t = 0; t < c.d; ++t) {
+                    const int l = pl.dim_order[(size_t)t];
+                    if (!c.periodic[(size_t)l] && c.c(pe.ref, l) != 0) mask |= 1u << l;
+                    if (r.kind == ISO_ROUND_SHIFT && l == r.dim) break;
+                }
+            he.de.meta = l2 | (mask << 8);
             if (first) { size0 = he.size; first = false; }
             uniform = uniform && he.size == size0;
-            min_log2 = std::min(min_log2, he.de.unit_log2);
+            min_log2 = std::min(min_log2, l2);
             rounds[ri].push_back(he);
         }
     }
@@ -289,7 +304,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             std::memset(&l, 0, sizeof(l));
             uint32_t k = 0;
             uint64_t total = 0;
-            if (uniform) {
+            if (uniform && !c.mesh) {
                 // regular blocks: every entry has `chunks` units of the request's common width
                 const uint64_t chunks = size0 >> min_log2;
                 const uint64_t per_entry = p * chunks;
@@ -317,8 +332,12 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 }
                 for (uint32_t q = 0; q < k; ++q) table.push_back(ents[done + q].de);
             } else {
-                // irregular blocks: as many entries as fit the 32-bit unit index
+                // irregular blocks, or a mesh: as many entries as fit the 32-bit unit index
                 l.kernel = kBlockKernel;
+                l.mesh = c.mesh;
+                l.block.shift_dim = r.kind == ISO_ROUND_SHIFT ? r.dim : -1;
+                for (int j = 0; j < c.d; ++j)
+                    if (c.periodic[(size_t)j]) l.block.periodic_mask |= 1u << j;
                 uint64_t row_units = 0;
                 prefixes.push_back(0);
                 while (done + k < ents.size()) {

@@ -44,9 +44,10 @@ struct alignas(16) DevEntry {
     uint64_t src_stride;   // bytes between consecutive ranks in the source buffer
     uint64_t dst_stride;
     uint32_t shift;        // SHIFT rounds: residue v; VECTOR rounds: neighbour index
-    uint32_t units;        // irregular launches: block size / unit width of this entry
-    uint32_t unit_log2;    // irregular launches: log2 of this entry's unit width in bytes
-    uint32_t pad;
+    uint32_t units;        // block launches: block size / unit width of this entry
+    uint32_t meta;         // block launches: bits 0-7 log2 of the unit width in bytes;
+                           // bits 8-23 (mesh) dimensions in which R - C^ref must be inside the mesh
+    uint32_t ref;          // mesh: neighbour whose coordinates decide whether the move happens
 };
 
 // Workgroup -> tile mapping.  The hardware hands consecutive workgroup ids to
@@ -169,16 +170,24 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
 // A rank's units are the concatenation of its entries' units; `prefix[e]` is
 // the first unit of entry e.  The flat index is split into (rank, unit in row),
 // the entry is found by binary search in the prefix array.
+//
+// MESH (Section 7, non-periodic dimensions): coordinates of non-periodic
+// dimensions are signed and nothing wraps there.  A move happens at rank R only
+// if R - C^ref stays inside the mesh in every dimension of the entry's mask
+// (the non-periodic dimensions routed up to and including this round in which
+// C^ref is non-zero); otherwise the destination keeps its content.
 struct BlockArgs {
     const DevEntry *entries;
     const uint32_t *prefix;    // [k + 1]
-    const uint32_t *offsets;   // [s][d] residues (VECTOR rounds)
+    const uint32_t *offsets;   // [s][d] effective coordinates (residues; signed where non-periodic)
     TileMap map;
     uint32_t total;            // p * row_units
     uint32_t k;
     uint32_t vector_round;     // 0: shift along one dimension, 1: full offset vector
     uint32_t inner, pj;        // shift rounds
-    int32_t d;                 // vector rounds
+    int32_t shift_dim;         // shift rounds: the dimension (-1: same-rank copy)
+    uint32_t periodic_mask;    // bit j set: dimension j wraps
+    int32_t d;
     FastDiv d_row, d_inner, d_pj;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
@@ -189,7 +198,12 @@ __device__ __forceinline__ void move_at(uint64_t dst, uint64_t src, uint32_t ch)
     move_unit<V>(reinterpret_cast<V *>(dst) + ch, reinterpret_cast<const V *>(src) + ch);
 }
 
-template <bool LDS>
+// steps back along a periodic dimension of size pj by residue v, from coordinate rj
+__device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t pj) {
+    return rj >= v ? -(int64_t)v : (int64_t)(pj - v);
+}
+
+template <bool LDS, bool MESH>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     __shared__ uint32_t lds_prefix[LDS ? kLdsEntries + 1 : 1];
@@ -214,24 +228,45 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     const DevEntry en = table[lo];
     const uint32_t ch = w - prefix[lo];
     int64_t srcR = R;
-    if (a.vector_round) {
+    if constexpr (MESH) {
+        // one pass over the coordinates of R: validity in the masked dimensions, and the source rank
+        const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
+        const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
+        const uint32_t *cvec = a.offsets + (size_t)en.shift * a.d;     // vector rounds: shift = neighbour
+        uint32_t rem = R;
+        for (int j = a.d - 1; j >= 0; --j) {
+            uint32_t q, rj;
+            fast_divmod(rem, a.d_dims[j], q, rj);
+            rem = q;
+            const uint32_t pj = a.d_dims[j].div;
+            if ((mask >> j) & 1u) {
+                const int64_t t = (int64_t)rj - (int64_t)(int32_t)cref[j];
+                if (t < 0 || t >= (int64_t)pj) return;                 // no source: leave the destination
+            }
+            const bool moves = a.vector_round || j == a.shift_dim;
+            if (moves) {
+                const uint32_t cj = a.vector_round ? cvec[j] : en.shift;
+                if ((a.periodic_mask >> j) & 1u) srcR += wrap_back(rj, cj, pj) * (int64_t)a.inner_of[j];
+                else srcR -= (int64_t)(int32_t)cj * (int64_t)a.inner_of[j];
+            }
+        }
+    } else if (a.vector_round) {
         const uint32_t *c = a.offsets + (size_t)en.shift * a.d;
         uint32_t rem = R;
         for (int j = a.d - 1; j >= 0; --j) {
             uint32_t q, rj;
             fast_divmod(rem, a.d_dims[j], q, rj);
             rem = q;
-            const uint32_t cj = c[j];
-            srcR += (rj >= cj ? -(int64_t)cj : (int64_t)(a.d_dims[j].div - cj)) * (int64_t)a.inner_of[j];
+            srcR += wrap_back(rj, c[j], a.d_dims[j].div) * (int64_t)a.inner_of[j];
         }
     } else {
         const uint32_t q = fast_div(R, a.d_inner);
         const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
-        srcR += (rj >= en.shift ? -(int64_t)en.shift : (int64_t)(a.pj - en.shift)) * (int64_t)a.inner;
+        srcR += wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner;
     }
     const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
     const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
-    switch (en.unit_log2) {
+    switch (en.meta & 0xFFu) {
         case 4: move_at<vec16_t>(dst, src, ch); break;
         case 3: move_at<vec8_t>(dst, src, ch); break;
         case 2: move_at<uint32_t>(dst, src, ch); break;

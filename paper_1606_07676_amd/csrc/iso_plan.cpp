@@ -35,7 +35,7 @@ int64_t Plan::entries() const {
     return n;
 }
 
-int build_comm(int d, const int32_t *dims, int s, const int32_t *rel, Comm &out) {
+int build_comm(int d, const int32_t *dims, const int32_t *periodic, int s, const int32_t *rel, Comm &out) {
     if (d < 1 || d > ISO_MAX_DIMS || !dims || s < 0 || (s > 0 && !rel)) return ISO_ERR_ARG;
     Comm c;
     c.d = d;
@@ -49,13 +49,21 @@ int build_comm(int d, const int32_t *dims, int s, const int32_t *rel, Comm &out)
     }
     c.inner.assign(d, 1);
     for (int j = d - 2; j >= 0; --j) c.inner[j] = c.inner[j + 1] * dims[j + 1];
+    c.periodic.assign(d, 1);
+    for (int j = 0; j < d && periodic; ++j) {
+        c.periodic[j] = periodic[j] != 0;
+        c.mesh = c.mesh || !c.periodic[j];
+    }
     c.raw.assign(rel, rel + (size_t)s * d);
     c.can.resize((size_t)s * d);
     c.values.assign(d, {});
     for (int i = 0; i < s; ++i)
         for (int j = 0; j < d; ++j) {
-            int64_t r = (int64_t)rel[(size_t)i * d + j] % dims[j];
-            if (r < 0) r += dims[j];
+            int64_t r = rel[(size_t)i * d + j];
+            if (c.periodic[j]) {
+                r %= dims[j];
+                if (r < 0) r += dims[j];
+            }
             c.can[(size_t)i * d + j] = (int32_t)r;
             if (r) c.values[j].push_back((int32_t)r);
         }
@@ -73,6 +81,8 @@ iso_plan_entry_t mk(int sb, int ss, int db, int ds, int shift, int nb) {
     iso_plan_entry_t e;
     e.src_buf = sb; e.src_slot = ss; e.dst_buf = db; e.dst_slot = ds;
     e.shift = shift; e.neighbor = nb;
+    e.ref = nb;
+    e.reserved = 0;
     return e;
 }
 
@@ -103,16 +113,24 @@ bool by_dst(const iso_plan_entry_t &a, const iso_plan_entry_t &b) {
 // all-to-all, message-combining
 // ---------------------------------------------------------------------------
 struct AlltoallState {
-    std::vector<int> hops, where, wslot;
-    int slot_in(int buf, int i) const { return buf == ISO_BUF_WORK ? wslot[i] : i; }
+    std::vector<int> hops, where, where_slot, wslot, wslot2;
+    bool mesh = false;
     // one hop of block i: parity rule of Algorithm 1
     iso_plan_entry_t hop(int i, int shift) {
         // received into the receive buffer when an odd number of hops remains,
-        // so that the last hop (one remaining) always lands there
-        const int dst = (hops[i] % 2 == 0) ? ISO_BUF_WORK : ISO_BUF_RECV;
-        const int src = where[i];
-        iso_plan_entry_t e = mk(src, slot_in(src, i), dst, slot_in(dst, i), shift, i);
+        // so that the last hop (one remaining) always lands there.  On a mesh the
+        // receive buffer takes only that last hop (a block in transit must not
+        // overwrite a receive block that is to stay untouched): earlier odd hops
+        // go to a second workspace slot.
+        int dst = (hops[i] % 2 == 0) ? ISO_BUF_WORK : ISO_BUF_RECV;
+        int dslot = dst == ISO_BUF_WORK ? wslot[i] : i;
+        if (mesh && dst == ISO_BUF_RECV && hops[i] > 1) {
+            dst = ISO_BUF_WORK;
+            dslot = wslot2[i];
+        }
+        iso_plan_entry_t e = mk(where[i], where_slot[i], dst, dslot, shift, i);
         where[i] = dst;
+        where_slot[i] = dslot;
         --hops[i];
         return e;
     }
@@ -122,13 +140,18 @@ void alltoall_prologue(const Comm &c, const Coords &co, AlltoallState &st, Plan 
     const int s = c.s;
     st.hops.assign(s, 0);
     st.where.assign(s, ISO_BUF_SEND);
+    st.where_slot.resize(s);
+    std::iota(st.where_slot.begin(), st.where_slot.end(), 0);
     st.wslot.assign(s, -1);
+    st.wslot2.assign(s, -1);
+    st.mesh = c.mesh;
     int nwork = 0;
     Round self;
     self.kind = ISO_ROUND_SELF;
     for (int i = 0; i < s; ++i) {
         for (int j = 0; j < c.d; ++j) st.hops[i] += co.raw ? std::abs(co.at(i, j)) : (co.at(i, j) != 0);
         if (st.hops[i] >= 2) st.wslot[i] = nwork++;     // only these ever sit in the intermediate buffer
+        if (c.mesh && st.hops[i] >= 3) st.wslot2[i] = nwork++;
         if (st.hops[i] == 0) self.entries.push_back(mk(ISO_BUF_SEND, i, ISO_BUF_RECV, i, 0, i));
     }
     pl.work_slots = nwork;
@@ -384,6 +407,7 @@ void plan_allgather_combined(const Comm &c, bool by_dim, Plan &pl) {
                 const Node &src = nodes[nodes[nd.parent].store];
                 if (nd.terminals.empty()) {
                     r.entries.push_back(mk(src.buf, src.slot, nd.buf, nd.slot, v, -1));
+                    r.entries.back().ref = sorted[(size_t)nd.first];
                 } else {
                     for (int i : nd.terminals)       // repeated offsets: one copy each
                         r.entries.push_back(mk(src.buf, src.slot, ISO_BUF_RECV, i, v, i));
@@ -438,6 +462,7 @@ void plan_allgather_onehop(const Comm &c, Plan &pl) {
                     if (remaining == 1) {
                         if (nd.terminals.empty()) {
                             r.entries.push_back(mk(at[q].first, at[q].second, nd.buf, nd.slot, shift, -1));
+                            r.entries.back().ref = sorted[(size_t)nd.first];
                         } else {
                             for (int i : nd.terminals)
                                 r.entries.push_back(mk(at[q].first, at[q].second, ISO_BUF_RECV, i, shift, i));
@@ -448,6 +473,7 @@ void plan_allgather_onehop(const Comm &c, Plan &pl) {
                                                                       : std::make_pair((int)ISO_BUF_WORK, nd.tmp_slot);
                         r.entries.push_back(mk(at[q].first, at[q].second, dst.first, dst.second, shift,
                                                nd.terminals.empty() ? -1 : nd.terminals[0]));
+                        r.entries.back().ref = sorted[(size_t)nd.first];
                         at[q] = dst;
                     }
                 }
@@ -501,6 +527,7 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
                 plan_allgather_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
             break;
         case ISO_ALG_ONEHOP:
+            if (c.mesh) return ISO_ERR_ARG;
             if (op == ISO_OP_ALLTOALL)
                 plan_alltoall_onehop(c, pl);
             else

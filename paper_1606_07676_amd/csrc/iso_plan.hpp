@@ -16,7 +16,10 @@ struct Comm {
     std::vector<int32_t> dims;       // p_j
     std::vector<int64_t> inner;      // prod_{l>j} p_l : rank stride of dimension j
     std::vector<int32_t> raw;        // s*d offsets as given
-    std::vector<int32_t> can;        // s*d offsets reduced into [0, p_j)
+    std::vector<int32_t> can;        // s*d effective coordinates: residue in [0, p_j) where the
+                                     // dimension is periodic, the raw signed value where it is not
+    std::vector<uint8_t> periodic;   // d flags
+    bool mesh = false;               // some dimension does not wrap
     std::vector<std::vector<int32_t>> values;  // per dimension: sorted distinct non-zero residues
 
     int32_t c(int i, int j) const { return can[(size_t)i * d + j]; }
@@ -42,7 +45,8 @@ struct Plan {
 };
 
 // Validates and canonicalises; returns ISO_SUCCESS or ISO_ERR_*.
-int build_comm(int d, const int32_t *dims, int s, const int32_t *rel, Comm &out);
+// `periodic` may be null (all dimensions wrap).
+int build_comm(int d, const int32_t *dims, const int32_t *periodic, int s, const int32_t *rel, Comm &out);
 
 // Order in which the allgather trie visits the dimensions: the identity order
 // unless the fewest-distinct-values-first order moves strictly fewer blocks.

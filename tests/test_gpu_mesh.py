@@ -1,0 +1,88 @@
+"""GPU parity on meshes (non-periodic dimensions): the HIP path against the CPU
+oracle, bit for bit; blocks without a source must keep their content."""
+import numpy as np
+import pytest
+import torch
+
+import iso_inputs as gen
+import paper_1606_07676_amd as iso
+from oracle import iso_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused"}
+
+MESHES = [
+    ((5,), (0,), [(1,), (-2,), (7,), (0,)]),
+    ((4, 3), (0, 0), gen.moore(2, 1)),
+    ((4, 3), (1, 0), gen.moore(2, 1) + [(0, 0), (5, 1), (1, 1)]),
+    ((3, 4, 2), (0, 1, 0), gen.moore(3, 1)),
+    ((6, 5), (0, 0), gen.von_neumann(2, 2)),
+    ((4, 4, 4), (0, 0, 1), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0), (3, 3, 2),
+                            (2, 0, 1), (2, 0, 2), (-1, 1, 1)]),
+    ((20, 20, 20), (0, 0, 0), gen.moore(3, 1)),          # several tiles; 27-point stencil on a box
+    ((70, 50), (0, 0), gen.moore(2, 2)),
+    ((4, 4, 4, 4), (0, 1, 0, 1), gen.random_distinct(4, -2, 2, 30, 5)),
+]
+
+
+def _run(dims, periodic, offsets, op, alg, m, send):
+    p, s = int(np.prod(dims)), len(offsets)
+    comm = iso.iso_neighborhood_create_mesh(dims, periodic, offsets)
+    wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+    recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=DEV)
+    work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+    init = iso.iso_neighbor_alltoall_init if op == iso.ISO_OP_ALLTOALL else iso.iso_neighbor_allgather_init
+    req = init(send, recv, m, work, comm, alg)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    iso.iso_request_free(req)
+    return recv
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("case", range(len(MESHES)))
+def test_mesh_alltoall_and_allgather_every_byte(case, alg):
+    dims, periodic, offsets = MESHES[case]
+    p, s = int(np.prod(dims)), len(offsets)
+    for m in (16, 48, 3, 256):
+        send_h = gen.alltoall_send(300 + case, p, s, m)
+        want = orc.alltoall_mesh(dims, periodic, offsets, send_h, np.full((p, s, m), 0xEE, np.uint8))
+        send = torch.from_numpy(send_h).to(DEV)
+        got = _run(dims, periodic, offsets, iso.ISO_OP_ALLTOALL, alg, m, send)
+        assert np.array_equal(got.cpu().numpy(), want), f"a2a dims={dims} periodic={periodic} m={m}"
+        assert np.array_equal(send.cpu().numpy(), send_h)
+        one_h = gen.allgather_send(300 + case, p, m)
+        wantg = orc.allgather_mesh(dims, periodic, offsets, one_h, np.full((p, s, m), 0xEE, np.uint8))
+        got = _run(dims, periodic, offsets, iso.ISO_OP_ALLGATHER, alg, m, torch.from_numpy(one_h).to(DEV))
+        assert np.array_equal(got.cpu().numpy(), wantg), f"ag dims={dims} periodic={periodic} m={m}"
+
+
+def test_mesh_irregular_blocks_and_refused_onehop():
+    dims, periodic, offsets = (9, 7, 5), (0, 0, 1), gen.moore(3, 1)
+    p, s = 315, 26
+    sizes = gen.stencil_block_sizes(offsets, 16)
+    sd, ext = gen.packed_displacements(sizes, 16)
+    rng = np.random.default_rng(3)
+    send_h = rng.integers(0, 256, size=(p, ext), dtype=np.uint8)
+    src, valid = orc.source_ranks_mesh(dims, periodic, offsets)
+    want = np.full((p, ext), 0xEE, np.uint8)
+    for i in range(s):
+        v = valid[:, i]
+        want[v, sd[i]:sd[i] + sizes[i]] = send_h[src[v, i], sd[i]:sd[i] + sizes[i]]
+    comm = iso.iso_neighborhood_create_mesh(dims, periodic, offsets)
+    send = torch.from_numpy(send_h).to(DEV)
+    for alg in ALGS:
+        recv = torch.full((p, ext), 0xEE, dtype=torch.uint8, device=DEV)
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+        work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, ext, recv, sizes, sd, ext, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        assert np.array_equal(recv.cpu().numpy(), want), ALG_NAMES[alg]
+        iso.iso_request_free(req)
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_init(send, send, 16, None, comm, iso.ISO_ALG_ONEHOP)
+    assert e.value.status == iso.ISO_ERR_ARG

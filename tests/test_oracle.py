@@ -392,3 +392,61 @@ def test_irregular_reduces_to_regular_and_to_roll(golden):
     assert sorted(set(big)) == _ints(golden["irregular_d3_base512_sizes"])
     assert abs(sum(big) / 1e6 - float(golden["irregular_d3_base512_total_MB"])) < 0.1
     assert (big.count(262144), big.count(512), big.count(1)) == (6, 12, 8)
+
+
+# ---------------------------------------------------------------- meshes
+
+MESHES = [
+    ((5,), (0,), [(1,), (-2,), (7,), (0,)]),
+    ((4, 3), (0, 0), gen.moore(2, 1)),
+    ((4, 3), (1, 0), gen.moore(2, 1) + [(0, 0), (5, 1)]),
+    ((3, 4, 2), (0, 1, 0), gen.moore(3, 1)),
+    ((6, 5), (0, 0), gen.von_neumann(2, 2)),
+]
+
+
+@pytest.mark.parametrize("dims,periodic,offsets", MESHES)
+def test_mesh_definition_by_slicing_and_by_push(dims, periodic, offsets):
+    p, s, d = int(np.prod(dims)), len(offsets), len(dims)
+    send = _rand_send(p, s, 3)
+    recv = orc.alltoall_mesh(dims, periodic, offsets, send, np.full_like(send, 0xEE))
+    # (a) array slicing: in a non-periodic dimension the receiving coordinates are
+    # [max(0,c), min(p, p+c)) and read from the same range moved back by c
+    for i, C in enumerate(offsets):
+        grid = send[:, i].reshape(tuple(dims) + (3,))
+        want = np.full_like(grid, 0xEE)
+        rolled = grid
+        dst_sl, src_sl = [], []
+        for j in range(d):
+            if periodic[j]:
+                rolled = np.roll(rolled, C[j], axis=j)
+                dst_sl.append(slice(None)); src_sl.append(slice(None))
+            else:
+                lo, hi = max(0, C[j]), min(dims[j], dims[j] + C[j])
+                dst_sl.append(slice(lo, max(lo, hi))); src_sl.append(slice(lo - C[j], max(lo, hi) - C[j]))
+        want[tuple(dst_sl)] = rolled[tuple(src_sl)]
+        assert np.array_equal(recv[:, i].reshape(want.shape), want), (i, C)
+    # (b) pure-Python push: every process hands block i to R + C^i if that process exists
+    coords = list(itertools.product(*[range(n) for n in dims]))
+    index = {c: r for r, c in enumerate(coords)}
+    want = [[None] * s for _ in coords]
+    for R, rc in enumerate(coords):
+        for i, C in enumerate(offsets):
+            t = tuple((rc[j] + C[j]) % dims[j] if periodic[j] else rc[j] + C[j] for j in range(d))
+            if t in index:
+                want[index[t]][i] = send[R, i]
+    for R in range(p):
+        for i in range(s):
+            exp = want[R][i] if want[R][i] is not None else np.full(3, 0xEE, np.uint8)
+            assert np.array_equal(recv[R, i], exp), (R, i)
+    one = np.ascontiguousarray(send[:, 0])
+    rep = np.repeat(one[:, None, :], s, axis=1)
+    assert np.array_equal(orc.allgather_mesh(dims, periodic, offsets, one, np.full_like(send, 0xEE)),
+                          orc.alltoall_mesh(dims, periodic, offsets, rep, np.full_like(send, 0xEE)))
+
+
+def test_fully_periodic_mesh_is_the_torus():
+    dims, offsets = (4, 3, 5), gen.moore(3, 1)
+    send = _rand_send(60, 26, 2)
+    got = orc.alltoall_mesh(dims, (1, 1, 1), offsets, send, np.zeros_like(send))
+    assert np.array_equal(got, orc.alltoall(dims, offsets, send))

@@ -306,3 +306,100 @@ def test_fastdiv_is_exact_on_the_host():
                                os.path.join(ROOT, "paper_1606_07676_amd", "csrc"), src, "-o", exe])
         out = subprocess.check_output([exe], text=True).split()
         assert int(out[0]) > 1_000_000 and int(out[1]) == 0
+
+
+# ---------------------------------------------------------------- meshes (non-periodic dimensions)
+
+MESHES = [
+    ((5,), (0,), [(1,), (-2,), (7,), (0,)]),
+    ((4, 3), (0, 0), gen.moore(2, 1)),
+    ((4, 3), (1, 0), gen.moore(2, 1) + [(0, 0), (5, 1), (1, 1)]),
+    ((3, 4, 2), (0, 1, 0), gen.moore(3, 1)),
+    ((6, 5), (0, 0), gen.von_neumann(2, 2)),
+    ((5, 4, 3), (0, 0, 0), gen.moore(3, 1)),
+    ((4, 4, 4), (0, 0, 1), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0), (3, 3, 2),
+                            (2, 0, 1), (2, 0, 2), (-1, 1, 1)]),
+]
+MESH_ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED]
+
+
+def _replay_mesh(dims, periodic, offsets, op, order, rounds, work_slots, send, m):
+    """Plan replay on a mesh: an entry's move happens at rank R only if R - C^ref is
+    inside the mesh in the non-periodic dimensions routed so far."""
+    d, s = len(dims), len(offsets)
+    p = int(np.prod(dims))
+    shape = tuple(dims)
+    eff = [tuple(c % n if per else c for c, n, per in zip(C, dims, periodic)) for C in offsets]
+    grid = np.indices(shape)
+    bufs = {
+        iso.ISO_BUF_SEND: send.reshape(shape + ((s, m) if op == iso.ISO_OP_ALLTOALL else (1, m))),
+        iso.ISO_BUF_RECV: np.full(shape + (max(s, 1), m), 0xEE, np.uint8),
+        iso.ISO_BUF_WORK: np.full(shape + (max(work_slots, 1), m), 0xDD, np.uint8),
+    }
+    for info, entries in rounds:
+        if info["kind"] == iso.ISO_ROUND_SHIFT:
+            routed = order[:order.index(info["dim"]) + 1]
+        elif info["kind"] == iso.ISO_ROUND_VECTOR:
+            routed = list(range(d))
+        else:
+            routed = []
+        reads, writes, staged = set(), set(), []
+        for e in entries:
+            src = bufs[e["src_buf"]][..., e["src_slot"], :]
+            C = eff[e["ref"]]
+            valid = np.ones(shape, bool)
+            for l in routed:
+                if not periodic[l] and C[l] != 0:
+                    t = grid[l] - C[l]
+                    valid &= (t >= 0) & (t < dims[l])
+            if info["kind"] == iso.ISO_ROUND_SHIFT:
+                assert e["shift"] == C[info["dim"]]
+                data = np.roll(src, e["shift"], axis=info["dim"])
+            elif info["kind"] == iso.ISO_ROUND_SELF:
+                data = src.copy()
+            else:
+                data = np.roll(src, eff[e["neighbor"]], axis=tuple(range(d)))
+            staged.append((e, data, valid))
+            reads.add((e["src_buf"], e["src_slot"]))
+            assert (e["dst_buf"], e["dst_slot"]) not in writes
+            writes.add((e["dst_buf"], e["dst_slot"]))
+            assert e["dst_buf"] != iso.ISO_BUF_SEND
+        assert not (reads & writes)
+        for e, data, valid in staged:
+            bufs[e["dst_buf"]][..., e["dst_slot"], :][valid] = data[valid]
+    return bufs[iso.ISO_BUF_RECV].reshape(p, max(s, 1), m)[:, :s]
+
+
+@pytest.mark.parametrize("alg", MESH_ALGS)
+@pytest.mark.parametrize("dims,periodic,offsets", MESHES)
+def test_mesh_plans_reach_the_oracle_result(dims, periodic, offsets, alg):
+    p, s, m = int(np.prod(dims)), len(offsets), 2
+    comm = iso.iso_neighborhood_create_mesh(dims, periodic, offsets)
+    for op in (iso.ISO_OP_ALLTOALL, iso.ISO_OP_ALLGATHER):
+        plan = iso.iso_plan_create(comm, op, alg)
+        pinfo = iso.iso_plan_info(plan)
+        rounds = _plan_rounds(plan)
+        order = pinfo["dim_order"][:len(dims)]
+        if op == iso.ISO_OP_ALLTOALL:
+            send = RNG.integers(0, 256, size=(p, s, m), dtype=np.uint8)
+            want = orc.alltoall_mesh(dims, periodic, offsets, send, np.full((p, s, m), 0xEE, np.uint8))
+            # a block in transit never sits in the receive buffer of a mesh
+            for info, entries in rounds:
+                for e in entries:
+                    assert not (e["src_buf"] == iso.ISO_BUF_RECV)
+        else:
+            send = RNG.integers(0, 256, size=(p, m), dtype=np.uint8)
+            want = orc.allgather_mesh(dims, periodic, offsets, send, np.full((p, s, m), 0xEE, np.uint8))
+        got = _replay_mesh(dims, periodic, offsets, op, order, rounds, pinfo["work_slots"], send, m)
+        assert np.array_equal(got, want), (dims, periodic, alg, op)
+
+
+def test_onehop_is_refused_on_a_mesh_and_full_periodicity_is_the_torus():
+    comm = iso.iso_neighborhood_create_mesh((4, 4), (1, 0), gen.moore(2, 1))
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_ONEHOP)
+    assert e.value.status == iso.ISO_ERR_ARG
+    a = iso.iso_neighborhood_create_mesh((4, 4), (1, 1), gen.moore(2, 1))
+    b = iso.iso_neighborhood_create((4, 4), gen.moore(2, 1))
+    pa, pb = iso.iso_plan_create(a, iso.ISO_OP_ALLTOALL), iso.iso_plan_create(b, iso.ISO_OP_ALLTOALL)
+    assert _plan_rounds(pa) == _plan_rounds(pb)
