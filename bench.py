@@ -140,25 +140,6 @@ def main():
     log(f"combined: {ms_per_step:.4f} ms/step, delivered {value:.1f} GB/s, moved "
         f"{moved / (ms_per_step * 1e-3) / 1e9:.1f} GB/s over {launches} launches")
 
-    # ---- verification of the timed configuration against the oracle -------------
-    from oracle import iso_oracle as orc
-    rng = np.random.default_rng(args.seed)
-    sample = np.unique(rng.integers(0, p, size=min(p, 512)))
-    src = torch.from_numpy(orc.source_ranks(cfg.dims, cfg.offsets, sample)).to(dev)
-    slots = torch.arange(s, device=dev)[None, :]
-    verified = True
-    for op in ops:
-        recv = bufs[op][1]
-        if op == iso.ISO_OP_ALLTOALL:
-            want = gen.block_bytes_torch(args.seed, src, slots, m, cfg.kind)
-        else:
-            want = gen.block_bytes_torch(args.seed ^ gen.ALLGATHER_TWEAK, src, torch.zeros_like(src), m, cfg.kind)
-        ok = bool(torch.equal(recv[torch.from_numpy(sample).to(dev)], want))
-        verified = verified and ok
-    if not verified:
-        log("bench.py: RESULT MISMATCH against the oracle; aborting")
-        sys.exit(3)
-
     # ---- per-launch durations of the round kernel (HIP events on the launch stream) ----
     per_round = []
     ev_steps = max(1, min(K, 50))
@@ -221,7 +202,7 @@ def main():
             "algorithm": "combined (torus-direct)", "seed": args.seed,
             "rounds": cinfo["rounds"], "delivered_bytes_per_step": delivered, "moved_bytes_per_step": moved,
         },
-        "verified_against_oracle": verified,
+        "verified_against_oracle": None,      # set by the CPU-oracle leg below
         "roofline": roofline,
         "per_round": per_round,
         "setup_ms": {"iso_neighborhood_create": round(t_create, 4),
@@ -294,9 +275,30 @@ def main():
         out["comparison"] = extras
         log(json.dumps(extras))
 
-    # ---- CPU baseline: the oracle's C twin on the host cores --------------------
+    # ---- CPU-oracle leg (the only part of this file that touches oracle/) --------
+    # (1) sampled ranks of the timed configuration against the oracle's source-rank table,
+    # (2) the oracle's C twin timed on the host cores, (3) its whole result against the GPU's.
     if not args.no_cpu_baseline:
         from oracle import c_twin
+        from oracle import iso_oracle as orc
+        for op in ops:                                   # one more step of the timed requests, from scratch
+            bufs[op][1].fill_(0xEE)
+        for r in reqs:
+            iso.iso_start(r, stream)
+        torch.cuda.synchronize()
+        rng = np.random.default_rng(args.seed)
+        sample = np.unique(rng.integers(0, p, size=min(p, 512)))
+        src = torch.from_numpy(orc.source_ranks(cfg.dims, cfg.offsets, sample)).to(dev)
+        slots = torch.arange(s, device=dev)[None, :]
+        for op in ops:
+            recv = bufs[op][1]
+            if op == iso.ISO_OP_ALLTOALL:
+                want = gen.block_bytes_torch(args.seed, src, slots, m, cfg.kind)
+            else:
+                want = gen.block_bytes_torch(args.seed ^ gen.ALLGATHER_TWEAK, src, torch.zeros_like(src), m, cfg.kind)
+            if not bool(torch.equal(recv[torch.from_numpy(sample).to(dev)], want)):
+                log("bench.py: RESULT MISMATCH against the oracle; aborting")
+                sys.exit(3)
         host = {}
         for op in ops:
             host[op] = bufs[op][0].cpu().numpy()
@@ -315,6 +317,7 @@ def main():
             if not np.array_equal(outs[op], bufs[op][1].cpu().numpy()):
                 log("bench.py: GPU result differs from the C oracle")
                 sys.exit(3)
+        out["verified_against_oracle"] = True
         t_med = median(times[1:]) if len(times) > 1 else times[0]
         out["cpu_baseline"] = {
             "value": round(delivered / t_med / 1e9, 3), "unit": "GB/s", "cores": int(used), "kind": "oracle",

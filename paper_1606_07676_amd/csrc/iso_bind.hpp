@@ -38,6 +38,8 @@ struct Launch {
     uint32_t grid;
     bool lds_table;
     bool mesh;
+    bool stream_loads;     // shift kernel: every source block is read exactly once in this launch
+
     ShiftArgs shift;
     VectorArgs vec;
     BlockArgs block;
@@ -141,12 +143,22 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k) {
     }
 }
 
+// Streaming loads exist for the shift kernel at the 16-byte width only (narrower
+// units are the slow path anyway).
 template <typename V, bool LDS>
 void enqueue_regular(const Launch &l, hipStream_t stream) {
-    if (l.kernel == kVectorKernel)
-        hipLaunchKernelGGL((vector_round_kernel<V, LDS>), dim3(l.grid), dim3(kThreads), 0, stream, l.vec);
-    else
-        hipLaunchKernelGGL((shift_round_kernel<V, LDS>), dim3(l.grid), dim3(kThreads), 0, stream, l.shift);
+    const dim3 grid(l.grid), block(kThreads);
+    if (l.kernel == kVectorKernel) {
+        hipLaunchKernelGGL((vector_round_kernel<V, LDS>), grid, block, 0, stream, l.vec);
+        return;
+    }
+    if constexpr (sizeof(V) == 16) {
+        if (l.stream_loads) {
+            hipLaunchKernelGGL((shift_round_kernel<V, LDS, true>), grid, block, 0, stream, l.shift);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((shift_round_kernel<V, LDS, false>), grid, block, 0, stream, l.shift);
 }
 
 template <typename V>
@@ -155,15 +167,19 @@ void enqueue_width(const Launch &l, hipStream_t stream) {
     else enqueue_regular<V, false>(l, stream);
 }
 
+template <bool LDS, bool MESH>
+void enqueue_block(const Launch &l, hipStream_t stream) {
+    hipLaunchKernelGGL((block_round_kernel<LDS, MESH>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
+}
+
 inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
     if (l.kernel == kBlockKernel) {
-        const dim3 grid(l.grid), block(kThreads);
         if (l.mesh) {
-            if (l.lds_table) hipLaunchKernelGGL((block_round_kernel<true, true>), grid, block, 0, stream, l.block);
-            else hipLaunchKernelGGL((block_round_kernel<false, true>), grid, block, 0, stream, l.block);
+            if (l.lds_table) enqueue_block<true, true>(l, stream);
+            else enqueue_block<false, true>(l, stream);
         } else {
-            if (l.lds_table) hipLaunchKernelGGL((block_round_kernel<true, false>), grid, block, 0, stream, l.block);
-            else hipLaunchKernelGGL((block_round_kernel<false, false>), grid, block, 0, stream, l.block);
+            if (l.lds_table) enqueue_block<true, false>(l, stream);
+            else enqueue_block<false, false>(l, stream);
         }
     } else {
         switch (vector_bytes) {
@@ -364,6 +380,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     b.inner_of[j] = (uint32_t)c.inner[j];
                 }
             }
+            l.stream_loads = op == ISO_OP_ALLTOALL && l.kernel == kShiftKernel;
             set_grid(l, (uint32_t)total, k);
             pending.push_back(pd);
             done += k;

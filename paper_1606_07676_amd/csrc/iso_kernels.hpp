@@ -21,9 +21,12 @@
 // per-lane unrolling (2, 4, 8 units per lane lose 3 %, 15 %, 50 %), for plain
 // copies as well as for these gathers.  Stores are streaming (non-temporal):
 // a block written in one round is next touched a whole round later (+8 % on
-// the all-to-all rounds).  Loads stay cacheable: allgather rounds and the
-// s-exchange read the same source block for several entries, and streaming
-// loads cost those 15-45 %.
+// the all-to-all rounds).  Loads are streaming too in the message-combining
+// rounds of an all-to-all, where every source block is read exactly once
+// (+1 to +4 %).  Everything else keeps cacheable loads: allgather rounds read
+// one source block for several entries (streaming loads cost them 15 %), and
+// the s-exchange kernels lose 25 % with streaming loads even when every block
+// is read once.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -92,9 +95,18 @@ struct VectorArgs {
 typedef uint32_t vec16_t __attribute__((ext_vector_type(4)));
 typedef uint32_t vec8_t __attribute__((ext_vector_type(2)));
 
-template <typename V>
-__device__ __forceinline__ void move_unit(V *dst, const V *src) {
-    __builtin_nontemporal_store(*src, dst);
+// One unit from byte address `src` to byte address `dst`, both in global memory
+// (the address space is spelled out so that the accesses are global_load /
+// global_store, not flat ones).  NTL: streaming load.
+template <typename V, bool NTL>
+__device__ __forceinline__ void move_unit(uint64_t dst, uint64_t src, uint32_t ch) {
+    typedef const V __attribute__((address_space(1))) *src_ptr;
+    typedef V __attribute__((address_space(1))) *dst_ptr;
+    const src_ptr sp = (src_ptr)src + ch;
+    V v;
+    if constexpr (NTL) v = __builtin_nontemporal_load(sp);
+    else v = *sp;
+    __builtin_nontemporal_store(v, (dst_ptr)dst + ch);
 }
 
 // Entry table of the launch: from LDS (staged once per workgroup) when it fits,
@@ -114,7 +126,7 @@ struct EntryTable {
     __device__ __forceinline__ DevEntry operator[](uint32_t e) const { return tab[e]; }
 };
 
-template <typename V, bool LDS>
+template <typename V, bool LDS, bool NTL>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
@@ -131,9 +143,7 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     // v steps back along the dimension, with wrap-around
     const int64_t back = rj >= en.shift ? -(int64_t)en.shift : (int64_t)(a.pj - en.shift);
     const uint64_t srcR = (uint64_t)((int64_t)R + back * (int64_t)a.inner);
-    const V *sp = reinterpret_cast<const V *>(en.src + srcR * en.src_stride) + ch;
-    V *dp = reinterpret_cast<V *>(en.dst + (uint64_t)R * en.dst_stride) + ch;
-    move_unit<V>(dp, sp);
+    move_unit<V, NTL>(en.dst + (uint64_t)R * en.dst_stride, en.src + srcR * en.src_stride, ch);
 }
 
 template <typename V, bool LDS>
@@ -159,9 +169,7 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
         const int64_t back = rj >= cj ? -(int64_t)cj : (int64_t)(a.d_dims[j].div - cj);
         srcR += back * (int64_t)a.inner[j];
     }
-    const V *sp = reinterpret_cast<const V *>(en.src + (uint64_t)srcR * en.src_stride) + ch;
-    V *dp = reinterpret_cast<V *>(en.dst + (uint64_t)R * en.dst_stride) + ch;
-    move_unit<V>(dp, sp);
+    move_unit<V, false>(en.dst + (uint64_t)R * en.dst_stride, en.src + (uint64_t)srcR * en.src_stride, ch);
 }
 
 // Irregular blocks (the v/w interfaces of Section 2): every entry has its own
@@ -192,11 +200,6 @@ struct BlockArgs {
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
-
-template <typename V>
-__device__ __forceinline__ void move_at(uint64_t dst, uint64_t src, uint32_t ch) {
-    move_unit<V>(reinterpret_cast<V *>(dst) + ch, reinterpret_cast<const V *>(src) + ch);
-}
 
 // steps back along a periodic dimension of size pj by residue v, from coordinate rj
 __device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t pj) {
@@ -267,11 +270,11 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
     const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
     switch (en.meta & 0xFFu) {
-        case 4: move_at<vec16_t>(dst, src, ch); break;
-        case 3: move_at<vec8_t>(dst, src, ch); break;
-        case 2: move_at<uint32_t>(dst, src, ch); break;
-        case 1: move_at<uint16_t>(dst, src, ch); break;
-        default: move_at<uint8_t>(dst, src, ch); break;
+        case 4: move_unit<vec16_t, false>(dst, src, ch); break;
+        case 3: move_unit<vec8_t, false>(dst, src, ch); break;
+        case 2: move_unit<uint32_t, false>(dst, src, ch); break;
+        case 1: move_unit<uint16_t, false>(dst, src, ch); break;
+        default: move_unit<uint8_t, false>(dst, src, ch); break;
     }
 }
 
