@@ -140,6 +140,24 @@ def main():
     log(f"combined: {ms_per_step:.4f} ms/step, delivered {value:.1f} GB/s, moved "
         f"{moved / (ms_per_step * 1e-3) / 1e9:.1f} GB/s over {launches} launches")
 
+    # ---- the paper's measurement protocol (Section 4): every repetition timed on its own
+    # after a synchronisation, outliers outside [Q1 - 3 IQR, Q3 + 3 IQR] dropped, median kept
+    reps = 100
+    rep_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in rep_ev:
+        torch.cuda.synchronize()
+        a.record(stream)
+        for r in reqs:
+            iso.iso_start(r, stream)
+        b.record(stream)
+    torch.cuda.synchronize()
+    rep_ms = sorted(a.elapsed_time(b) for a, b in rep_ev)
+    q1, q3 = rep_ms[reps // 4], rep_ms[(3 * reps) // 4]
+    kept = [t for t in rep_ms if q1 - 3 * (q3 - q1) <= t <= q3 + 3 * (q3 - q1)]
+    protocol = {"repetitions": reps, "kept_after_tukey_3iqr": len(kept), "median_ms": round(median(kept), 5),
+                "min_ms": round(kept[0], 5), "max_ms": round(kept[-1], 5),
+                "delivered_GBs_at_median": round(delivered / median(kept) / 1e6, 1)}
+
     # ---- per-launch durations of the round kernel (HIP events on the launch stream) ----
     per_round = []
     ev_steps = max(1, min(K, 50))
@@ -204,6 +222,7 @@ def main():
         },
         "verified_against_oracle": None,      # set by the CPU-oracle leg below
         "roofline": roofline,
+        "isolated_repetitions": protocol,
         "per_round": per_round,
         "setup_ms": {"iso_neighborhood_create": round(t_create, 4),
                      **{f"iso_neighbor_{op_name[op]}_init": round(t, 4) for op, t in zip(ops, t_init)}},

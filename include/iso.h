@@ -236,6 +236,19 @@ int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t s
                                  void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                  iso_request_t *req);
 
+/* The paper's w variants (per-neighbour datatypes, displacements in bytes): with
+ * every size and displacement already in bytes they are the v calls under their
+ * second name; same arguments, same behaviour. */
+int iso_neighbor_alltoallw_init(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                const size_t *recv_displs, size_t recv_extent, void *workspace,
+                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                iso_request_t *req);
+int iso_neighbor_allgatherw_init(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                 const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                 void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                 iso_request_t *req);
+
 /* Enqueues the launches of one collective on `hip_stream` (a hipStream_t; NULL
  * = the default stream) and returns without waiting.  Rounds are ordered by the
  * stream.  Calls on one request must not overlap in time on the device. */

@@ -96,6 +96,10 @@ _PROTOTYPES = {
                                      ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgatherv_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
                                       ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_alltoallw_init": ([_VP, _VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
+                                     ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_allgatherw_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
+                                      ctypes.POINTER(_VP)], _I),
     "iso_start": ([_VP, _VP], _I),
     "iso_start_range": ([_VP, _I, _I, _VP], _I),
     "iso_request_set_graph": ([_VP, _I], _I),
@@ -320,30 +324,56 @@ def iso_workspace_bytes_v(comm, op, algorithm, sizes):
     return out.value
 
 
-def iso_neighbor_alltoallv_init(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
-                                recv_displs, recv_extent, workspace, comm,
-                                algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+def _alltoallv(name, sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes, recv_displs,
+               recv_extent, workspace, comm, algorithm, workspace_bytes):
     ss, sd, rs, rd = (_size_array(x) for x in (send_sizes, send_displs, recv_sizes, recv_displs))
     h = ctypes.c_void_p()
     p = lambda a: a.ctypes.data if a.size else None
-    st = load_library().iso_neighbor_alltoallv_init(
+    st = getattr(load_library(), name)(
         _ptr(sendbuf), p(ss), p(sd), send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
         _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
-    _check(st, "iso_neighbor_alltoallv_init")
+    _check(st, name)
     return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def _allgatherv(name, sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs, recv_extent,
+                workspace, comm, algorithm, workspace_bytes):
+    rs, rd = _size_array(recv_sizes), _size_array(recv_displs)
+    h = ctypes.c_void_p()
+    p = lambda a: a.ctypes.data if a.size else None
+    st = getattr(load_library(), name)(
+        _ptr(sendbuf), send_size, send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
+    _check(st, name)
+    return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def iso_neighbor_alltoallv_init(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
+                                recv_displs, recv_extent, workspace, comm,
+                                algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    return _alltoallv("iso_neighbor_alltoallv_init", sendbuf, send_sizes, send_displs, send_extent, recvbuf,
+                      recv_sizes, recv_displs, recv_extent, workspace, comm, algorithm, workspace_bytes)
+
+
+def iso_neighbor_alltoallw_init(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
+                                recv_displs, recv_extent, workspace, comm,
+                                algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    return _alltoallv("iso_neighbor_alltoallw_init", sendbuf, send_sizes, send_displs, send_extent, recvbuf,
+                      recv_sizes, recv_displs, recv_extent, workspace, comm, algorithm, workspace_bytes)
 
 
 def iso_neighbor_allgatherv_init(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs,
                                  recv_extent, workspace, comm, algorithm=ISO_ALG_COMBINED,
                                  workspace_bytes=None):
-    rs, rd = _size_array(recv_sizes), _size_array(recv_displs)
-    h = ctypes.c_void_p()
-    p = lambda a: a.ctypes.data if a.size else None
-    st = load_library().iso_neighbor_allgatherv_init(
-        _ptr(sendbuf), send_size, send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
-        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
-    _check(st, "iso_neighbor_allgatherv_init")
-    return Request(h.value, (sendbuf, recvbuf, workspace))
+    return _allgatherv("iso_neighbor_allgatherv_init", sendbuf, send_size, send_extent, recvbuf, recv_sizes,
+                       recv_displs, recv_extent, workspace, comm, algorithm, workspace_bytes)
+
+
+def iso_neighbor_allgatherw_init(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs,
+                                 recv_extent, workspace, comm, algorithm=ISO_ALG_COMBINED,
+                                 workspace_bytes=None):
+    return _allgatherv("iso_neighbor_allgatherw_init", sendbuf, send_size, send_extent, recvbuf, recv_sizes,
+                       recv_displs, recv_extent, workspace, comm, algorithm, workspace_bytes)
 
 
 def iso_start(req, stream=None):

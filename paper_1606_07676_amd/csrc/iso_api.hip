@@ -19,7 +19,7 @@ thread_local int g_last_hip_error = 0;
 
 struct iso_comm_s {
     iso::Comm c;
-    int64_t allgather_moves = 0;
+    int64_t allgather_moves = -1;        // computed by the first iso_neighborhood_info
 };
 
 struct iso_plan_s {
@@ -138,28 +138,30 @@ int iso_neighborhood_create_mesh(int d, const int32_t *dims, const int32_t *peri
             delete h;
             return st;
         }
-        (void)iso::allgather_dim_order(h->c, &h->allgather_moves);
         *comm = h;
         return ISO_SUCCESS;
     });
 }
 
 int iso_neighborhood_info(iso_comm_t comm, iso_comm_info_t *info) {
-    if (!comm || !info) return ISO_ERR_ARG;
-    const iso::Comm &c = comm->c;
-    info->d = c.d;
-    info->s = c.s;
-    info->p = c.p;
-    info->rounds = c.rounds();
-    info->self_slots = 0;
-    info->alltoall_moves = 0;
-    for (int i = 0; i < c.s; ++i) {
-        const int n = c.nnz(i);
-        info->alltoall_moves += n;
-        info->self_slots += n == 0;
-    }
-    info->allgather_moves = comm->allgather_moves;
-    return ISO_SUCCESS;
+    return guarded([&]() -> int {
+        if (!comm || !info) return ISO_ERR_ARG;
+        const iso::Comm &c = comm->c;
+        if (comm->allgather_moves < 0) (void)iso::allgather_dim_order(c, &comm->allgather_moves);
+        info->d = c.d;
+        info->s = c.s;
+        info->p = c.p;
+        info->rounds = c.rounds();
+        info->self_slots = 0;
+        info->alltoall_moves = 0;
+        for (int i = 0; i < c.s; ++i) {
+            const int n = c.nnz(i);
+            info->alltoall_moves += n;
+            info->self_slots += n == 0;
+        }
+        info->allgather_moves = comm->allgather_moves;
+        return ISO_SUCCESS;
+    });
 }
 
 int iso_neighborhood_free(iso_comm_t *comm) {
@@ -319,6 +321,24 @@ int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t s
         return make_request(ISO_OP_ALLGATHER, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm,
                             algorithm, req);
     });
+}
+
+int iso_neighbor_alltoallw_init(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                const size_t *recv_displs, size_t recv_extent, void *workspace,
+                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                iso_request_t *req) {
+    return iso_neighbor_alltoallv_init(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
+                                       recv_displs, recv_extent, workspace, workspace_bytes, comm, algorithm,
+                                       req);
+}
+
+int iso_neighbor_allgatherw_init(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                 const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                 void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                 iso_request_t *req) {
+    return iso_neighbor_allgatherv_init(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs,
+                                        recv_extent, workspace, workspace_bytes, comm, algorithm, req);
 }
 
 int iso_request_set_graph(iso_request_t req, int enable) {

@@ -105,6 +105,38 @@ def test_allgatherv_every_byte(case, alg):
         iso.iso_request_free(req)
 
 
+def test_w_names_are_the_v_calls():
+    """The paper's w variants (byte displacements, one datatype per neighbour) under
+    their own names: same result as the oracle's definition."""
+    dims, offsets = CASES[0]
+    p, s = int(np.prod(dims)), len(offsets)
+    sizes, sd, sext, rd, rext = _layouts(s, "stencil16")
+    comm = _comm(dims, offsets)
+    send_h = RNG.integers(0, 256, size=(p, sext), dtype=np.uint8)
+    want = orc.alltoallv(dims, offsets, send_h, sizes, sd, np.full((p, rext), 0xEE, np.uint8), rd)
+    send = torch.from_numpy(send_h).to(DEV)
+    recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+    work = torch.empty(max(iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, sizes), 16),
+                       dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_alltoallw_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    assert np.array_equal(recv.cpu().numpy(), want)
+    iso.iso_request_free(req)
+    m = 48
+    gd = [i * 64 for i in range(s)]
+    gext = 64 * s
+    gsend_h = RNG.integers(0, 256, size=(p, 64), dtype=np.uint8)
+    gwant = orc.allgatherv(dims, offsets, gsend_h, m, np.full((p, gext), 0xEE, np.uint8), gd)
+    gsend = torch.from_numpy(gsend_h).to(DEV)
+    grecv = torch.full((p, gext), 0xEE, dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_allgatherw_init(gsend, m, 64, grecv, [m] * s, gd, gext, None, comm)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    assert np.array_equal(grecv.cpu().numpy(), gwant)
+    iso.iso_request_free(req)
+
+
 def test_irregular_argument_checks():
     dims, offsets = (4, 4), gen.moore(2, 1)
     comm = _comm(dims, offsets)
