@@ -308,6 +308,23 @@ def test_fastdiv_is_exact_on_the_host():
         assert int(out[0]) > 1_000_000 and int(out[1]) == 0
 
 
+def test_schedule_builder_under_address_and_ub_sanitizers():
+    """The host-side schedule builder (pure C++) compiled with -fsanitize=address,undefined
+    and driven with seeded random tori, meshes and neighbourhoods through every algorithm."""
+    csrc = os.path.join(ROOT, "paper_1606_07676_amd", "csrc")
+    with tempfile.TemporaryDirectory() as td:
+        exe = os.path.join(td, "plan_san")
+        subprocess.check_call(["g++", "-O1", "-g", "-std=c++17", "-fsanitize=address,undefined",
+                               "-fno-sanitize-recover=all", "-static-libasan", "-static-libubsan", "-I", csrc, "-I", os.path.join(ROOT, "include"),
+                               os.path.join(ROOT, "tests", "plan_sanitizer_driver.cpp"),
+                               os.path.join(csrc, "iso_plan.cpp"), "-o", exe])
+        # the sanitizer runtimes are linked statically: a preloaded library may then come first
+        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0:verify_asan_link_order=0")
+        out = subprocess.run([exe], env=env, stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+        assert out.returncode == 0, out.stderr[-2000:]
+        assert int(out.stdout.split()[0]) > 3000
+
+
 # ---------------------------------------------------------------- meshes (non-periodic dimensions)
 
 MESHES = [
@@ -403,3 +420,62 @@ def test_onehop_is_refused_on_a_mesh_and_full_periodicity_is_the_torus():
     b = iso.iso_neighborhood_create((4, 4), gen.moore(2, 1))
     pa, pb = iso.iso_plan_create(a, iso.ISO_OP_ALLTOALL), iso.iso_plan_create(b, iso.ISO_OP_ALLTOALL)
     assert _plan_rounds(pa) == _plan_rounds(pb)
+
+
+# ---------------------------------------------------------------- seeded random sweep
+
+def _random_case(rng, mesh):
+    d = int(rng.integers(1, 5))
+    dims = tuple(int(x) for x in rng.integers(1, 6, size=d))
+    s = int(rng.integers(0, 13))
+    span = int(rng.integers(1, 8))
+    offsets = [tuple(int(x) for x in rng.integers(-span, span + 1, size=d)) for _ in range(s)]
+    for _ in range(int(rng.integers(0, 3))):                       # repeats and the zero vector
+        if offsets:
+            offsets.append(offsets[int(rng.integers(0, len(offsets)))])
+    if rng.integers(0, 3) == 0:
+        offsets.append((0,) * d)
+    periodic = tuple(int(x) for x in rng.integers(0, 2, size=d)) if mesh else (1,) * d
+    return dims, periodic, offsets
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_torus_plans_reach_the_oracle_result(seed):
+    """Random tori (sizes 1..5, so offsets alias and wrap several times), random signed
+    offsets with repeats and zero vectors: every algorithm's plan, replayed on the host,
+    gives the definition, without hazards."""
+    rng = np.random.default_rng(1000 + seed)
+    dims, _, offsets = _random_case(rng, mesh=False)
+    p, s, m = int(np.prod(dims)), len(offsets), 2
+    comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, len(dims)))
+    a2a = rng.integers(0, 256, size=(p, s, m), dtype=np.uint8)
+    ag = rng.integers(0, 256, size=(p, m), dtype=np.uint8)
+    want_a2a, want_ag = orc.alltoall(dims, offsets, a2a), orc.allgather(dims, offsets, ag)
+    for alg in ALGS:
+        for op, send, want in ((iso.ISO_OP_ALLTOALL, a2a, want_a2a), (iso.ISO_OP_ALLGATHER, ag, want_ag)):
+            plan = iso.iso_plan_create(comm, op, alg)
+            pinfo = iso.iso_plan_info(plan)
+            recv, written = _replay(dims, offsets, op, _plan_rounds(plan), pinfo["work_slots"], send, m)
+            assert np.array_equal(recv, want), (dims, offsets, alg, op)
+            assert {(iso.ISO_BUF_RECV, i) for i in range(s)} <= written
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_mesh_plans_reach_the_oracle_result(seed):
+    rng = np.random.default_rng(2000 + seed)
+    dims, periodic, offsets = _random_case(rng, mesh=True)
+    p, s, m = int(np.prod(dims)), len(offsets), 2
+    comm = iso.iso_neighborhood_create_mesh(dims, periodic, np.asarray(offsets, np.int32).reshape(s, len(dims)))
+    a2a = rng.integers(0, 256, size=(p, s, m), dtype=np.uint8)
+    ag = rng.integers(0, 256, size=(p, m), dtype=np.uint8)
+    keep = np.full((p, s, m), 0xEE, np.uint8)
+    want_a2a = orc.alltoall_mesh(dims, periodic, offsets, a2a, keep.copy())
+    want_ag = orc.allgather_mesh(dims, periodic, offsets, ag, keep.copy())
+    for alg in MESH_ALGS:
+        for op, send, want in ((iso.ISO_OP_ALLTOALL, a2a, want_a2a), (iso.ISO_OP_ALLGATHER, ag, want_ag)):
+            plan = iso.iso_plan_create(comm, op, alg)
+            pinfo = iso.iso_plan_info(plan)
+            order = pinfo["dim_order"][:len(dims)]
+            got = _replay_mesh(dims, periodic, offsets, op, order, _plan_rounds(plan), pinfo["work_slots"],
+                               send, m)
+            assert np.array_equal(got, want), (dims, periodic, offsets, alg, op)
