@@ -33,6 +33,27 @@ def build(verbose=False):
     return LIB_PATH
 
 
+SANITIZER_DRIVER_SRC = os.path.join(ROOT, "tests", "abi_sanitizer_driver.cpp")
+SANITIZER_DRIVER = os.path.join(ROOT, "tests", "abi_sanitizer_driver")
+
+
+def build_abi_sanitizer_driver(verbose=False):
+    """The C ABI test driver with the library's host code under ASan + UBSan (sanitizers on
+    the host pass only; the device code is the normal gfx950 build).  Returns its path."""
+    cmd = ["hipcc", "-O1", "-g", "-std=c++17", "--offload-arch=gfx950",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-static-libsan",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+           SANITIZER_DRIVER_SRC, *SOURCES, "-o", SANITIZER_DRIVER]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    lines = [l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l]
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
+    return SANITIZER_DRIVER
+
+
 def is_stale():
     if not os.path.exists(LIB_PATH):
         return True
