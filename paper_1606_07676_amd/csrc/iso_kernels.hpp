@@ -23,10 +23,10 @@
 // a block written in one round is next touched a whole round later (+8 % on
 // the all-to-all rounds).  Loads are streaming too in the message-combining
 // rounds of an all-to-all, where every source block is read exactly once
-// (+1 to +4 %).  Everything else keeps cacheable loads: allgather rounds read
+// (+1 to +9 %).  Everything else keeps cacheable loads: allgather rounds read
 // one source block for several entries (streaming loads cost them 15 %), and
-// the s-exchange kernels lose 25 % with streaming loads even when every block
-// is read once.
+// the s-exchange kernels lose 25 % with streaming loads where the buffers fit
+// the last-level cache and gain nothing where they do not.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -126,6 +126,45 @@ struct EntryTable {
     __device__ __forceinline__ DevEntry operator[](uint32_t e) const { return tab[e]; }
 };
 
+// steps back along a periodic dimension of size pj by residue v, from coordinate rj
+__device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t pj) {
+    return rj >= v ? -(int64_t)v : (int64_t)(pj - v);
+}
+
+// Source rank of R for a move by the full offset vector c[0..d): R (-) c on the torus.
+// Up to kUnrolledDims dimensions the loop over the dimensions is unrolled, so that the
+// per-dimension launch constants are read at fixed kernel-argument offsets (scalar
+// registers) and the d loads of c are issued together; indexing those arrays with a
+// run-time j costs a dependent scalar load per dimension and, at one unit per lane, a
+// third of the kernel's throughput.
+constexpr int kUnrolledDims = 6;
+
+// Rank arithmetic is done modulo 2^32: ranks are below 2^31 and every true result lies in
+// [0, p), so the wrapped intermediate values are harmless.
+__device__ __forceinline__ uint32_t vector_source_rank(uint32_t R, const uint32_t *__restrict__ c, int32_t d,
+                                                       const FastDiv (&d_dims)[ISO_MAX_DIMS],
+                                                       const uint32_t (&inner)[ISO_MAX_DIMS]) {
+    uint32_t srcR = R, rem = R;
+    auto step = [&](int j, uint32_t cj) {
+        uint32_t q, rj;
+        fast_divmod(rem, d_dims[j], q, rj);
+        rem = q;
+        srcR -= cj * inner[j];                                   // cj steps back ...
+        if (rj < cj) srcR += d_dims[j].div * inner[j];           // ... around the ring
+    };
+    if (d <= kUnrolledDims) {
+        uint32_t cj[kUnrolledDims];
+#pragma unroll
+        for (int j = 0; j < kUnrolledDims; ++j) cj[j] = j < d ? c[j] : 0u;
+#pragma unroll
+        for (int j = kUnrolledDims - 1; j >= 0; --j)
+            if (j < d) step(j, cj[j]);
+    } else {
+        for (int j = d - 1; j >= 0; --j) step(j, c[j]);
+    }
+    return srcR;
+}
+
 template <typename V, bool LDS, bool NTL>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
@@ -141,8 +180,7 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
     const DevEntry en = table[e];
     // v steps back along the dimension, with wrap-around
-    const int64_t back = rj >= en.shift ? -(int64_t)en.shift : (int64_t)(a.pj - en.shift);
-    const uint64_t srcR = (uint64_t)((int64_t)R + back * (int64_t)a.inner);
+    const uint64_t srcR = (uint64_t)((int64_t)R + wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner);
     move_unit<V, NTL>(en.dst + (uint64_t)R * en.dst_stride, en.src + srcR * en.src_stride, ch);
 }
 
@@ -158,17 +196,7 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
     fast_divmod(u, a.d_chunks, t, ch);
     fast_divmod(t, a.d_k, R, e);
     const DevEntry en = table[e];
-    const uint32_t *c = a.offsets + (size_t)en.shift * a.d;
-    int64_t srcR = R;
-    uint32_t rem = R;
-    for (int j = a.d - 1; j >= 0; --j) {
-        uint32_t q, rj;
-        fast_divmod(rem, a.d_dims[j], q, rj);
-        rem = q;
-        const uint32_t cj = c[j];
-        const int64_t back = rj >= cj ? -(int64_t)cj : (int64_t)(a.d_dims[j].div - cj);
-        srcR += back * (int64_t)a.inner[j];
-    }
+    const uint32_t srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner);
     move_unit<V, false>(en.dst + (uint64_t)R * en.dst_stride, en.src + (uint64_t)srcR * en.src_stride, ch);
 }
 
@@ -201,11 +229,6 @@ struct BlockArgs {
     uint32_t inner_of[ISO_MAX_DIMS];
 };
 
-// steps back along a periodic dimension of size pj by residue v, from coordinate rj
-__device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t pj) {
-    return rj >= v ? -(int64_t)v : (int64_t)(pj - v);
-}
-
 template <bool LDS, bool MESH>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
@@ -230,42 +253,51 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     }
     const DevEntry en = table[lo];
     const uint32_t ch = w - prefix[lo];
-    int64_t srcR = R;
+    uint32_t srcR = R;                                    // modulo 2^32, see vector_source_rank
     if constexpr (MESH) {
         // one pass over the coordinates of R: validity in the masked dimensions, and the source rank
         const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
         const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
-        const uint32_t *cvec = a.offsets + (size_t)en.shift * a.d;     // vector rounds: shift = neighbour
+        // vector rounds: en.shift is the neighbour whose offsets move the block; in shift rounds it is
+        // the distance itself, so no row of the offset table may be addressed with it
+        const uint32_t *cvec = a.vector_round ? a.offsets + (size_t)en.shift * a.d : cref;
         uint32_t rem = R;
-        for (int j = a.d - 1; j >= 0; --j) {
+        bool has_source = true;
+        auto step = [&](int j, uint32_t cref_j, uint32_t cvec_j) {
             uint32_t q, rj;
             fast_divmod(rem, a.d_dims[j], q, rj);
             rem = q;
             const uint32_t pj = a.d_dims[j].div;
             if ((mask >> j) & 1u) {
-                const int64_t t = (int64_t)rj - (int64_t)(int32_t)cref[j];
-                if (t < 0 || t >= (int64_t)pj) return;                 // no source: leave the destination
+                const int64_t t = (int64_t)rj - (int64_t)(int32_t)cref_j;
+                if (t < 0 || t >= (int64_t)pj) has_source = false;
             }
-            const bool moves = a.vector_round || j == a.shift_dim;
-            if (moves) {
-                const uint32_t cj = a.vector_round ? cvec[j] : en.shift;
-                if ((a.periodic_mask >> j) & 1u) srcR += wrap_back(rj, cj, pj) * (int64_t)a.inner_of[j];
-                else srcR -= (int64_t)(int32_t)cj * (int64_t)a.inner_of[j];
+            if (a.vector_round || j == a.shift_dim) {
+                const uint32_t cj = a.vector_round ? cvec_j : en.shift;
+                srcR -= cj * a.inner_of[j];               // signed where the dimension does not wrap
+                if (((a.periodic_mask >> j) & 1u) && rj < cj) srcR += pj * a.inner_of[j];
             }
+        };
+        if (a.d <= kUnrolledDims) {
+            uint32_t cr[kUnrolledDims], cv[kUnrolledDims];
+#pragma unroll
+            for (int j = 0; j < kUnrolledDims; ++j) {
+                cr[j] = j < a.d ? cref[j] : 0u;
+                cv[j] = j < a.d ? cvec[j] : 0u;
+            }
+#pragma unroll
+            for (int j = kUnrolledDims - 1; j >= 0; --j)
+                if (j < a.d) step(j, cr[j], cv[j]);
+        } else {
+            for (int j = a.d - 1; j >= 0; --j) step(j, cref[j], cvec[j]);
         }
+        if (!has_source) return;                          // leave the destination as it is
     } else if (a.vector_round) {
-        const uint32_t *c = a.offsets + (size_t)en.shift * a.d;
-        uint32_t rem = R;
-        for (int j = a.d - 1; j >= 0; --j) {
-            uint32_t q, rj;
-            fast_divmod(rem, a.d_dims[j], q, rj);
-            rem = q;
-            srcR += wrap_back(rj, c[j], a.d_dims[j].div) * (int64_t)a.inner_of[j];
-        }
+        srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner_of);
     } else {
         const uint32_t q = fast_div(R, a.d_inner);
         const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
-        srcR += wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner;
+        srcR = (uint32_t)((int64_t)R + wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner);
     }
     const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
     const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
