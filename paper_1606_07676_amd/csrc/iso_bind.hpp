@@ -38,7 +38,7 @@ struct Launch {
     uint32_t grid;
     bool lds_table;
     bool mesh;
-    bool stream_loads;     // shift kernel: every source block is read exactly once in this launch
+    bool stream_loads;     // every source block is read exactly once in this launch: non-temporal loads
 
     ShiftArgs shift;
     VectorArgs vec;
@@ -169,7 +169,9 @@ void enqueue_width(const Launch &l, hipStream_t stream) {
 
 template <bool LDS, bool MESH>
 void enqueue_block(const Launch &l, hipStream_t stream) {
-    hipLaunchKernelGGL((block_round_kernel<LDS, MESH>), dim3(l.grid), dim3(kThreads), 0, stream, l.block);
+    const dim3 grid(l.grid), block(kThreads);
+    if (l.stream_loads) hipLaunchKernelGGL((block_round_kernel<LDS, MESH, true>), grid, block, 0, stream, l.block);
+    else hipLaunchKernelGGL((block_round_kernel<LDS, MESH, false>), grid, block, 0, stream, l.block);
 }
 
 inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
@@ -367,6 +369,10 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
                 total = row_units * p;
                 BlockArgs &b = l.block;
+                b.equal_units = ents[done].de.units;
+                for (uint32_t q = 1; q < k; ++q)
+                    if (ents[done + q].de.units != b.equal_units) b.equal_units = 0;
+                b.d_units = make_fastdiv(b.equal_units ? b.equal_units : 1u);
                 b.vector_round = r.kind == ISO_ROUND_VECTOR;
                 b.d_row = make_fastdiv((uint32_t)row_units);
                 const bool shift = r.kind == ISO_ROUND_SHIFT;
@@ -380,7 +386,10 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     b.inner_of[j] = (uint32_t)c.inner[j];
                 }
             }
-            l.stream_loads = op == ISO_OP_ALLTOALL && l.kernel == kShiftKernel;
+            // streaming loads: all-to-all shift rounds of equal blocks (irregular blocks and the
+            // s-exchange kernels are faster with cacheable loads)
+            l.stream_loads = op == ISO_OP_ALLTOALL && r.kind != ISO_ROUND_VECTOR &&
+                             (l.kernel == kShiftKernel || (l.kernel == kBlockKernel && l.block.equal_units));
             set_grid(l, (uint32_t)total, k);
             pending.push_back(pd);
             done += k;

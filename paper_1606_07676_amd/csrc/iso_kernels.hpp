@@ -224,12 +224,13 @@ struct BlockArgs {
     int32_t shift_dim;         // shift rounds: the dimension (-1: same-rank copy)
     uint32_t periodic_mask;    // bit j set: dimension j wraps
     int32_t d;
-    FastDiv d_row, d_inner, d_pj;
+    uint32_t equal_units;      // != 0: every entry of the launch has this many units (no search)
+    FastDiv d_row, d_inner, d_pj, d_units;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
 
-template <bool LDS, bool MESH>
+template <bool LDS, bool MESH, bool NTL>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     __shared__ uint32_t lds_prefix[LDS ? kLdsEntries + 1 : 1];
@@ -245,14 +246,19 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     if (u >= a.total) return;
     uint32_t R, w;
     fast_divmod(u, a.d_row, R, w);
-    uint32_t lo = 0, hi = a.k;                 // largest e with prefix[e] <= w
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (prefix[mid] <= w) lo = mid;
-        else hi = mid;
+    uint32_t lo = 0, ch;
+    if (a.equal_units) {                       // equal blocks (a mesh with regular blocks): plain division
+        fast_divmod(w, a.d_units, lo, ch);
+    } else {
+        uint32_t hi = a.k;                     // largest e with prefix[e] <= w
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (prefix[mid] <= w) lo = mid;
+            else hi = mid;
+        }
+        ch = w - prefix[lo];
     }
     const DevEntry en = table[lo];
-    const uint32_t ch = w - prefix[lo];
     uint32_t srcR = R;                                    // modulo 2^32, see vector_source_rank
     if constexpr (MESH) {
         // one pass over the coordinates of R: validity in the masked dimensions, and the source rank
@@ -302,7 +308,7 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
     const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
     switch (en.meta & 0xFFu) {
-        case 4: move_unit<vec16_t, false>(dst, src, ch); break;
+        case 4: move_unit<vec16_t, NTL>(dst, src, ch); break;
         case 3: move_unit<vec8_t, false>(dst, src, ch); break;
         case 2: move_unit<uint32_t, false>(dst, src, ch); break;
         case 1: move_unit<uint16_t, false>(dst, src, ch); break;
