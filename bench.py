@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="2", help="workload: 1..5 (default 2, the one the metric is quoted on)")
     ap.add_argument("--m", type=int, default=None, help="override the block size in bytes")
+    ap.add_argument("--layout", choices=("rank", "slot"), default="rank",
+                    help="buffers of the timed requests: rank = the paper's [p][s][m] (default), slot = [s][p][m]")
     ap.add_argument("--seed", type=int, default=2016)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparison algorithms and the copy ceiling")
@@ -99,14 +101,26 @@ def main():
             send = gen.allgather_send_torch(args.seed, p, m, cfg.kind, device=dev)
         recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=dev)
         bufs[op] = (send, recv)
-
-    def make_request(op, alg):
+    # buffers of the timed requests; with --layout slot the same blocks as [s][p][m]
+    slot = args.layout == "slot"
+    timed = {}
+    for op in ops:
         send, recv = bufs[op]
+        if slot:
+            tsend = send.permute(1, 0, 2).contiguous() if op == iso.ISO_OP_ALLTOALL else send
+            timed[op] = (tsend, torch.full((s, p, m), 0xEE, dtype=torch.uint8, device=dev))
+        else:
+            timed[op] = (send, recv)
+
+    def make_request(op, alg, timed_buffers=False):
+        send, recv = timed[op] if timed_buffers else bufs[op]
         wsb = iso.iso_workspace_bytes(comm, op, alg, m)
         work = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
-        init = iso.iso_neighbor_alltoall_init if op == iso.ISO_OP_ALLTOALL else iso.iso_neighbor_allgather_init
+        init = iso.iso_neighbor_alltoall_init_layout if op == iso.ISO_OP_ALLTOALL else \
+            iso.iso_neighbor_allgather_init_layout
+        layout = iso.ISO_LAYOUT_SLOT_MAJOR if (timed_buffers and slot) else iso.ISO_LAYOUT_RANK_MAJOR
         t = time.perf_counter()
-        req = init(send, recv, m, work, comm, alg)
+        req = init(send, recv, m, layout, work, comm, alg)
         return req, (time.perf_counter() - t) * 1e3
 
     def time_steps(reqs, steps, warmup):
@@ -125,7 +139,7 @@ def main():
 
     reqs, t_init = [], []
     for op in ops:
-        r, t = make_request(op, iso.ISO_ALG_COMBINED)
+        r, t = make_request(op, iso.ISO_ALG_COMBINED, timed_buffers=True)
         reqs.append(r)
         t_init.append(t)
     infos = [iso.iso_request_info(r) for r in reqs]
@@ -195,7 +209,7 @@ def main():
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": recorded_traffic(cfg.name, m),
+        "traffic": None if slot else recorded_traffic(cfg.name, m),
         "algorithmic_bytes_per_launch": int(alg_bytes_per_launch),
         "avg_launch_us": round(avg_launch_ms * 1e3, 2),
         "launches_per_step": launches,
@@ -217,6 +231,7 @@ def main():
         "config": {
             "workload": f"{cfg.name}: torus {'x'.join(map(str, cfg.dims))} (p={p}), s={s}, m={m} B, "
                         f"{'+'.join(cfg.ops)} per step, message-combining schedule, one kernel per round",
+            "layout": "[s][p][m] (slot-major)" if slot else "[p][s][m] (rank-major, the paper's)",
             "algorithm": "combined (torus-direct)", "seed": args.seed,
             "rounds": cinfo["rounds"], "delivered_bytes_per_step": delivered, "moved_bytes_per_step": moved,
         },
@@ -291,6 +306,34 @@ def main():
                 iso.iso_request_free(r)
                 del iwork
             del isend, irecv
+        # the same collectives on slot-major buffers ([s][p][m], one plane per neighbour): every
+        # block-move is a dense stream on both sides, whatever m is
+        sm_reqs = {}
+        for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
+                          ("sx_fused", iso.ISO_ALG_SX_FUSED)):
+            rs, keepalive = [], []
+            for op in ops:
+                if op == iso.ISO_OP_ALLTOALL:
+                    sm_send = torch.empty((s, p, m), dtype=torch.uint8, device=dev).fill_(5)
+                    init = iso.iso_neighbor_alltoall_init_layout
+                else:
+                    sm_send = bufs[op][0]
+                    init = iso.iso_neighbor_allgather_init_layout
+                sm_recv = torch.empty((s, p, m), dtype=torch.uint8, device=dev)
+                wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+                sm_work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+                rs.append(init(sm_send, sm_recv, m, iso.ISO_LAYOUT_SLOT_MAJOR, sm_work, comm, alg))
+                keepalive += [sm_send, sm_recv, sm_work]
+            ms = time_steps(rs, ksteps, 3) / ksteps
+            mv = sum(iso.iso_request_info(r)["bytes_read"] * 2 for r in rs)
+            extras[f"slot_major_{name}"] = {
+                "ms_per_step": round(ms, 5), "delivered_GBs": round(delivered / ms / 1e6, 1),
+                "moved_GBs": round(mv / ms / 1e6, 1), "frac_of_peak": round(mv / ms / 1e6 / HBM_PEAK_GBS, 4),
+                "launches": sum(iso.iso_request_info(r)["launches"] for r in rs)}
+            for r in rs:
+                iso.iso_request_free(r)
+            del rs, keepalive
+            torch.cuda.empty_cache()
         # the same torus taken as a box (no dimension wraps, Section 7): blocks whose source lies
         # outside stay untouched; moved bytes are nominal (every entry counted at every rank)
         if args.config == "2":
@@ -317,7 +360,7 @@ def main():
         from oracle import c_twin
         from oracle import iso_oracle as orc
         for op in ops:                                   # one more step of the timed requests, from scratch
-            bufs[op][1].fill_(0xEE)
+            timed[op][1].fill_(0xEE)
         for r in reqs:
             iso.iso_start(r, stream)
         torch.cuda.synchronize()
@@ -326,7 +369,7 @@ def main():
         src = torch.from_numpy(orc.source_ranks(cfg.dims, cfg.offsets, sample)).to(dev)
         slots = torch.arange(s, device=dev)[None, :]
         for op in ops:
-            recv = bufs[op][1]
+            recv = timed[op][1].permute(1, 0, 2) if slot else timed[op][1]      # view as [p][s][m]
             if op == iso.ISO_OP_ALLTOALL:
                 want = gen.block_bytes_torch(args.seed, src, slots, m, cfg.kind)
             else:
@@ -349,7 +392,8 @@ def main():
             if (time.perf_counter() - t_begin > args.cpu_seconds and len(times) >= 3) or len(times) >= 5000:
                 break
         for op in ops:                                   # the two sides agree on the whole buffer
-            if not np.array_equal(outs[op], bufs[op][1].cpu().numpy()):
+            got = timed[op][1].permute(1, 0, 2) if slot else timed[op][1]
+            if not np.array_equal(outs[op], got.cpu().numpy()):
                 log("bench.py: GPU result differs from the C oracle")
                 sys.exit(3)
         out["verified_against_oracle"] = True

@@ -85,6 +85,16 @@ enum iso_round_kind {
     ISO_ROUND_VECTOR = 2         /* every entry moves by its full offset vector (s-exchange)   */
 };
 
+enum iso_layout {                /* how the p*s blocks of a regular collective lie in a buffer  */
+    /* the paper's layout (Section 2): every process holds its s blocks back to
+     * back in neighbour order, processes back to back: [p][s][m]                */
+    ISO_LAYOUT_RANK_MAJOR = 0,
+    /* one plane per neighbour: block i of all processes back to back, planes in
+     * neighbour order: [s][p][m].  Every block-move of a round then reads and
+     * writes a dense stream whatever m is (the layout the workspace always has). */
+    ISO_LAYOUT_SLOT_MAJOR = 1
+};
+
 typedef struct iso_comm_s    *iso_comm_t;     /* torus + neighbourhood                    */
 typedef struct iso_plan_s    *iso_plan_t;     /* schedule for (comm, op, algorithm)       */
 typedef struct iso_request_s *iso_request_t;  /* schedule bound to buffers and block size */
@@ -207,6 +217,19 @@ int iso_neighbor_alltoall_init(const void *sendbuf, void *recvbuf, size_t m,
 int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m,
                                 void *workspace, size_t workspace_bytes,
                                 iso_comm_t comm, int algorithm, iso_request_t *req);
+
+/* The same two collectives with the layout of the caller's buffers chosen by
+ * `layout` (enum iso_layout).  ISO_LAYOUT_RANK_MAJOR is exactly the calls above.
+ * ISO_LAYOUT_SLOT_MAJOR: sendbuf (all-to-all) and recvbuf are [s][p][m]: block
+ * (R,i) sits at offset (i*p + R)*m; the allgather sendbuf stays [p][m].  Results
+ * are the same blocks at their new places: recv(R,i) = send(R (-) C^i, i).  All
+ * other rules (alignment, overlap, workspace size, errors) are unchanged. */
+int iso_neighbor_alltoall_init_layout(const void *sendbuf, void *recvbuf, size_t m, int layout,
+                                      void *workspace, size_t workspace_bytes,
+                                      iso_comm_t comm, int algorithm, iso_request_t *req);
+int iso_neighbor_allgather_init_layout(const void *sendbuf, void *recvbuf, size_t m, int layout,
+                                       void *workspace, size_t workspace_bytes,
+                                       iso_comm_t comm, int algorithm, iso_request_t *req);
 
 /* ---- irregular variants (Section 2, second interface listing) ---------------
  * Per-neighbour block sizes and displacements, in bytes, the same on every

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     ISO_OP_ALLTOALL, ISO_OP_ALLGATHER,
     ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP,
     ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK,
+    ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR,
     ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR,
     ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP,
     ISO_ERR_NOMEM, ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_MAX_DIMS,
@@ -16,6 +17,7 @@ from .binding import (  # noqa: F401
     iso_neighborhood_create, iso_neighborhood_create_mesh, iso_neighborhood_info, iso_neighborhood_free,
     iso_plan_create, iso_plan_info, iso_plan_round, iso_plan_entries, iso_plan_free,
     iso_workspace_bytes, iso_neighbor_alltoall_init, iso_neighbor_allgather_init,
+    iso_neighbor_alltoall_init_layout, iso_neighbor_allgather_init_layout,
     iso_workspace_bytes_v, iso_neighbor_alltoallv_init, iso_neighbor_allgatherv_init,
     iso_neighbor_alltoallw_init, iso_neighbor_allgatherw_init,
     iso_start, iso_start_range, iso_request_set_graph, iso_wait, iso_request_info, iso_request_plan, iso_request_free,

@@ -16,6 +16,7 @@ ISO_MAX_DIMS = 16
 ISO_OP_ALLTOALL, ISO_OP_ALLGATHER = 0, 1
 ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP = 0, 1, 2, 3, 4
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
+ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR = 0, 1
 ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR = 0, 1, 2
 
 
@@ -91,6 +92,8 @@ _PROTOTYPES = {
     "iso_workspace_bytes": ([_VP, _I, _I, _SZ, ctypes.POINTER(_SZ)], _I),
     "iso_neighbor_alltoall_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgather_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_alltoall_init_layout": ([_VP, _VP, _SZ, _I, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_allgather_init_layout": ([_VP, _VP, _SZ, _I, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_workspace_bytes_v": ([_VP, _I, _I, _VP, ctypes.POINTER(_SZ)], _I),
     "iso_neighbor_alltoallv_init": ([_VP, _VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
                                      ctypes.POINTER(_VP)], _I),
@@ -309,6 +312,27 @@ def iso_neighbor_allgather_init(sendbuf, recvbuf, m, workspace, comm,
                                 algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
     return _init("iso_neighbor_allgather_init", sendbuf, recvbuf, m, workspace, workspace_bytes,
                  comm, algorithm)
+
+
+def _init_layout(name, sendbuf, recvbuf, m, layout, workspace, workspace_bytes, comm, algorithm):
+    h = ctypes.c_void_p()
+    fn = getattr(load_library(), name)
+    st = fn(_ptr(sendbuf), _ptr(recvbuf), m, layout, _ptr(workspace), _nbytes(workspace, workspace_bytes),
+            comm.handle, algorithm, ctypes.byref(h))
+    _check(st, name)
+    return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def iso_neighbor_alltoall_init_layout(sendbuf, recvbuf, m, layout, workspace, comm,
+                                      algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    return _init_layout("iso_neighbor_alltoall_init_layout", sendbuf, recvbuf, m, layout, workspace,
+                        workspace_bytes, comm, algorithm)
+
+
+def iso_neighbor_allgather_init_layout(sendbuf, recvbuf, m, layout, workspace, comm,
+                                       algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    return _init_layout("iso_neighbor_allgather_init_layout", sendbuf, recvbuf, m, layout, workspace,
+                        workspace_bytes, comm, algorithm)
 
 
 def _size_array(values):

@@ -51,19 +51,27 @@ int guarded(F &&f) {
     }
 }
 
-// Regular blocks: s blocks of m bytes back to back in neighbour order.
-iso::Layout regular_layout(const iso::Comm &c, int op, size_t m) {
+// Regular blocks of m bytes.  Rank-major: a process's s blocks back to back in neighbour
+// order, [p][s][m].  Slot-major: one plane of p blocks per neighbour, [s][p][m]; the
+// distance between consecutive ranks is then m and block i starts i*p*m into the buffer.
+iso::Layout regular_layout(const iso::Comm &c, int op, size_t m, int layout = ISO_LAYOUT_RANK_MAJOR) {
     iso::Layout lay;
     const size_t s = (size_t)c.s;
+    const uint64_t slot = layout == ISO_LAYOUT_SLOT_MAJOR ? (uint64_t)c.p * m : m;
+    lay.slot_major = layout == ISO_LAYOUT_SLOT_MAJOR;
     lay.size.assign(s, m);
     lay.send_displ.resize(s);
     lay.recv_displ.resize(s);
     for (size_t i = 0; i < s; ++i) {
-        lay.send_displ[i] = op == ISO_OP_ALLTOALL ? i * m : 0;
-        lay.recv_displ[i] = i * m;
+        lay.send_displ[i] = op == ISO_OP_ALLTOALL ? i * slot : 0;
+        lay.recv_displ[i] = i * slot;
     }
-    lay.send_extent = lay.send_span = op == ISO_OP_ALLTOALL ? s * m : (s ? m : 0);
-    lay.recv_extent = lay.recv_span = s * m;
+    const uint64_t row = lay.slot_major ? m : s * m;           // bytes between consecutive ranks
+    const uint64_t span = s ? (s - 1) * slot + m : 0;           // first to last byte of one rank's blocks
+    lay.send_extent = op == ISO_OP_ALLTOALL ? row : (s ? m : 0);
+    lay.send_span = op == ISO_OP_ALLTOALL ? span : (s ? m : 0);
+    lay.recv_extent = row;
+    lay.recv_span = span;
     return lay;
 }
 
@@ -107,15 +115,15 @@ int make_request(int op, const iso::Layout &lay, const void *sendbuf, void *recv
     return ISO_SUCCESS;
 }
 
-int init_regular(int op, const void *sendbuf, void *recvbuf, size_t m, void *workspace,
+int init_regular(int op, const void *sendbuf, void *recvbuf, size_t m, int layout, void *workspace,
                  size_t workspace_bytes, iso_comm_t comm, int algorithm, iso_request_t *out) {
     if (!out) return ISO_ERR_ARG;
     *out = nullptr;
-    if (!comm) return ISO_ERR_ARG;
+    if (!comm || (layout != ISO_LAYOUT_RANK_MAJOR && layout != ISO_LAYOUT_SLOT_MAJOR)) return ISO_ERR_ARG;
     const uint64_t p = (uint64_t)comm->c.p, s = (uint64_t)comm->c.s;
     if (m && p > (~(uint64_t)0 >> 2) / std::max<uint64_t>(1, s) / m) return ISO_ERR_TOO_LARGE;
-    return make_request(op, regular_layout(comm->c, op, m), sendbuf, recvbuf, workspace, workspace_bytes,
-                        comm, algorithm, out);
+    return make_request(op, regular_layout(comm->c, op, m, layout), sendbuf, recvbuf, workspace,
+                        workspace_bytes, comm, algorithm, out);
 }
 
 }  // namespace
@@ -255,8 +263,8 @@ int iso_neighbor_alltoall_init(const void *sendbuf, void *recvbuf, size_t m, voi
                                size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                iso_request_t *req) {
     return guarded([&]() -> int {
-        return init_regular(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
-                            algorithm, req);
+        return init_regular(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, ISO_LAYOUT_RANK_MAJOR, workspace,
+                            workspace_bytes, comm, algorithm, req);
     });
 }
 
@@ -264,7 +272,25 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m, vo
                                 size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                 iso_request_t *req) {
     return guarded([&]() -> int {
-        return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, workspace, workspace_bytes, comm,
+        return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, ISO_LAYOUT_RANK_MAJOR, workspace,
+                            workspace_bytes, comm, algorithm, req);
+    });
+}
+
+int iso_neighbor_alltoall_init_layout(const void *sendbuf, void *recvbuf, size_t m, int layout,
+                                      void *workspace, size_t workspace_bytes, iso_comm_t comm,
+                                      int algorithm, iso_request_t *req) {
+    return guarded([&]() -> int {
+        return init_regular(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, layout, workspace, workspace_bytes, comm,
+                            algorithm, req);
+    });
+}
+
+int iso_neighbor_allgather_init_layout(const void *sendbuf, void *recvbuf, size_t m, int layout,
+                                       void *workspace, size_t workspace_bytes, iso_comm_t comm,
+                                       int algorithm, iso_request_t *req) {
+    return guarded([&]() -> int {
+        return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, layout, workspace, workspace_bytes, comm,
                             algorithm, req);
     });
 }

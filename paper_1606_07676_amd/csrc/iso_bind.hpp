@@ -50,7 +50,8 @@ struct Launch {
 struct Layout {
     std::vector<uint64_t> size, send_displ, recv_displ;
     uint64_t send_extent = 0, recv_extent = 0;
-    uint64_t send_span = 0, recv_span = 0;    // bytes of a row that blocks actually cover
+    uint64_t send_span = 0, recv_span = 0;    // first to last byte of one rank's blocks
+    bool slot_major = false;                  // regular blocks laid out [s][p][m]: ranks are m bytes apart
 };
 
 struct Range {
@@ -331,10 +332,13 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 total = per_entry * k;
                 l.kernel = r.kind == ISO_ROUND_VECTOR ? kVectorKernel : kShiftKernel;
                 const FastDiv dch = make_fastdiv((uint32_t)chunks), dk = make_fastdiv(k);
+                const FastDiv dp = make_fastdiv((uint32_t)p);
                 if (l.kernel == kVectorKernel) {
                     l.vec.d = c.d;
                     l.vec.d_chunks = dch;
                     l.vec.d_k = dk;
+                    l.vec.d_p = dp;
+                    l.vec.entry_major = lay.slot_major;
                     for (int j = 0; j < c.d; ++j) {
                         l.vec.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
                         l.vec.inner[j] = (uint32_t)c.inner[j];
@@ -345,6 +349,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.shift.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
                     l.shift.d_chunks = dch;
                     l.shift.d_k = dk;
+                    l.shift.d_p = dp;
+                    l.shift.entry_major = lay.slot_major;
                     l.shift.d_inner = make_fastdiv(l.shift.inner);
                     l.shift.d_pj = make_fastdiv(l.shift.pj);
                 }

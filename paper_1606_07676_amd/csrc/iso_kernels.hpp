@@ -13,7 +13,9 @@
 // [p][s][m] buffers and the workspace without pack or unpack copies.
 //
 // Work decomposition: the launch is a flat array of `vector-width` byte units
-// ordered (rank, entry, chunk-in-block), chunk fastest, ONE unit per lane.
+// ordered (rank, entry, chunk-in-block), chunk fastest, ONE unit per lane
+// (slot-major buffers, one plane of p blocks per neighbour: (entry, rank, chunk),
+// so that every wavefront access is one dense kilobyte of one plane).
 // Consecutive lanes touch consecutive 16-byte pieces of one block, then the next
 // block of the same rank: every wavefront load/store covers whole blocks, and a
 // 256-lane workgroup covers 4 KiB of consecutive units.  Measured on MI355X,
@@ -77,7 +79,8 @@ struct ShiftArgs {
     uint32_t k;            // entries in this launch
     uint32_t inner;        // rank stride of the shifted dimension
     uint32_t pj;           // its size
-    FastDiv d_chunks, d_k, d_inner, d_pj;
+    uint32_t entry_major;  // unit order (entry, rank, chunk) instead of (rank, entry, chunk)
+    FastDiv d_chunks, d_k, d_inner, d_pj, d_p;
 };
 
 struct VectorArgs {
@@ -87,7 +90,8 @@ struct VectorArgs {
     uint32_t total;
     uint32_t k;
     int32_t d;
-    FastDiv d_chunks, d_k;
+    uint32_t entry_major;
+    FastDiv d_chunks, d_k, d_p;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner[ISO_MAX_DIMS];
 };
@@ -175,7 +179,8 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
-    fast_divmod(t, a.d_k, R, e);
+    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
+    else fast_divmod(t, a.d_k, R, e);
     const uint32_t q = fast_div(R, a.d_inner);
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
     const DevEntry en = table[e];
@@ -194,7 +199,8 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
-    fast_divmod(t, a.d_k, R, e);
+    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
+    else fast_divmod(t, a.d_k, R, e);
     const DevEntry en = table[e];
     const uint32_t srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner);
     move_unit<V, false>(en.dst + (uint64_t)R * en.dst_stride, en.src + (uint64_t)srcR * en.src_stride, ch);
