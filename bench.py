@@ -306,6 +306,26 @@ def main():
                 iso.iso_request_free(r)
                 del iwork
             del isend, irecv
+            # the same blocks as one dense plane per neighbour (slot-major)
+            pd, at = [], 0
+            for sz in sizes:
+                pd.append(at)
+                at += -(-p * sz // 16) * 16
+            psend = torch.empty(at, dtype=torch.uint8, device=dev).fill_(3)
+            precv = torch.empty(at, dtype=torch.uint8, device=dev)
+            for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("sx_fused", iso.ISO_ALG_SX_FUSED)):
+                wsb = iso.iso_workspace_bytes_v(icomm, iso.ISO_OP_ALLTOALL, alg, sizes)
+                iwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+                r = iso.iso_neighbor_alltoallv_init_layout(psend, sizes, pd, 0, precv, sizes, pd, 0,
+                                                           iso.ISO_LAYOUT_SLOT_MAJOR, iwork, icomm, alg)
+                ms = time_steps([r], ksteps, 3) / ksteps
+                inf = iso.iso_request_info(r)
+                extras[f"alltoallv_stencil_base64_slot_major_{name}"] = {
+                    "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
+                    "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+                iso.iso_request_free(r)
+                del iwork
+            del psend, precv
         # the same collectives on slot-major buffers ([s][p][m], one plane per neighbour): every
         # block-move is a dense stream on both sides, whatever m is
         sm_reqs = {}

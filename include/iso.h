@@ -259,6 +259,22 @@ int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t s
                                  void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                  iso_request_t *req);
 
+/* The irregular calls with the layout of the caller's buffers chosen by `layout`.
+ * ISO_LAYOUT_RANK_MAJOR: exactly the calls above.  ISO_LAYOUT_SLOT_MAJOR: one
+ * plane per neighbour; block i of rank R sits at displs[i] + R * sizes[i], plane i
+ * covers [displs[i], displs[i] + p * sizes[i]); the extents are ignored except
+ * send_extent of the allgather, whose send buffer stays one row per rank.  Receive
+ * planes must not overlap (ISO_ERR_OVERLAP). */
+int iso_neighbor_alltoallv_init_layout(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                       size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                       const size_t *recv_displs, size_t recv_extent, int layout,
+                                       void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                       iso_request_t *req);
+int iso_neighbor_allgatherv_init_layout(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                        const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                        int layout, void *workspace, size_t workspace_bytes, iso_comm_t comm,
+                                        int algorithm, iso_request_t *req);
+
 /* The paper's w variants (per-neighbour datatypes, displacements in bytes): with
  * every size and displacement already in bytes they are the v calls under their
  * second name; same arguments, same behaviour. */

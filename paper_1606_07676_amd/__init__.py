@@ -20,6 +20,7 @@ from .binding import (  # noqa: F401
     iso_neighbor_alltoall_init_layout, iso_neighbor_allgather_init_layout,
     iso_workspace_bytes_v, iso_neighbor_alltoallv_init, iso_neighbor_allgatherv_init,
     iso_neighbor_alltoallw_init, iso_neighbor_allgatherw_init,
+    iso_neighbor_alltoallv_init_layout, iso_neighbor_allgatherv_init_layout,
     iso_start, iso_start_range, iso_request_set_graph, iso_wait, iso_request_info, iso_request_plan, iso_request_free,
     iso_error_string, iso_last_hip_error, iso_copy_reference,
 )

@@ -99,6 +99,10 @@ _PROTOTYPES = {
                                      ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgatherv_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
                                       ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_alltoallv_init_layout": ([_VP, _VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _I, _VP, _SZ, _VP, _I,
+                                            ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_allgatherv_init_layout": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _I, _VP, _SZ, _VP, _I,
+                                             ctypes.POINTER(_VP)], _I),
     "iso_neighbor_alltoallw_init": ([_VP, _VP, _VP, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
                                      ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgatherw_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
@@ -369,6 +373,32 @@ def _allgatherv(name, sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv
         _ptr(sendbuf), send_size, send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent,
         _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
     _check(st, name)
+    return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def iso_neighbor_alltoallv_init_layout(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes,
+                                       recv_displs, recv_extent, layout, workspace, comm,
+                                       algorithm=ISO_ALG_COMBINED, workspace_bytes=None):
+    ss, sd, rs, rd = (_size_array(x) for x in (send_sizes, send_displs, recv_sizes, recv_displs))
+    h = ctypes.c_void_p()
+    p = lambda a: a.ctypes.data if a.size else None
+    st = load_library().iso_neighbor_alltoallv_init_layout(
+        _ptr(sendbuf), p(ss), p(sd), send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent, layout,
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
+    _check(st, "iso_neighbor_alltoallv_init_layout")
+    return Request(h.value, (sendbuf, recvbuf, workspace))
+
+
+def iso_neighbor_allgatherv_init_layout(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs,
+                                        recv_extent, layout, workspace, comm, algorithm=ISO_ALG_COMBINED,
+                                        workspace_bytes=None):
+    rs, rd = _size_array(recv_sizes), _size_array(recv_displs)
+    h = ctypes.c_void_p()
+    p = lambda a: a.ctypes.data if a.size else None
+    st = load_library().iso_neighbor_allgatherv_init_layout(
+        _ptr(sendbuf), send_size, send_extent, _ptr(recvbuf), p(rs), p(rd), recv_extent, layout,
+        _ptr(workspace), _nbytes(workspace, workspace_bytes), comm.handle, algorithm, ctypes.byref(h))
+    _check(st, "iso_neighbor_allgatherv_init_layout")
     return Request(h.value, (sendbuf, recvbuf, workspace))
 
 

@@ -126,6 +126,81 @@ int init_regular(int op, const void *sendbuf, void *recvbuf, size_t m, int layou
                         workspace_bytes, comm, algorithm, out);
 }
 
+// Planes of a slot-major irregular buffer: plane i holds block i of all p ranks back to back,
+// [displ_i, displ_i + p * size_i).  Receive planes must not overlap.
+int check_planes(const std::vector<uint64_t> &size, const std::vector<uint64_t> &displ, uint64_t p, bool disjoint) {
+    const uint64_t limit = ~uint64_t(0) >> 2;
+    std::vector<std::pair<uint64_t, uint64_t>> iv;
+    for (size_t i = 0; i < size.size(); ++i) {
+        if (!size[i]) continue;
+        if (size[i] > limit / std::max<uint64_t>(1, p) || displ[i] > limit) return ISO_ERR_TOO_LARGE;
+        iv.emplace_back(displ[i], displ[i] + p * size[i]);
+    }
+    if (disjoint) {
+        std::sort(iv.begin(), iv.end());
+        for (size_t q = 1; q < iv.size(); ++q)
+            if (iv[q].first < iv[q - 1].second) return ISO_ERR_OVERLAP;
+    }
+    return ISO_SUCCESS;
+}
+
+int init_alltoallv(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs, size_t send_extent,
+                   void *recvbuf, const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                   int layout, void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                   iso_request_t *req) {
+    if (!req) return ISO_ERR_ARG;
+    *req = nullptr;
+    if (!comm || (layout != ISO_LAYOUT_RANK_MAJOR && layout != ISO_LAYOUT_SLOT_MAJOR)) return ISO_ERR_ARG;
+    const size_t s = (size_t)comm->c.s;
+    if (s && (!send_sizes || !send_displs || !recv_sizes || !recv_displs)) return ISO_ERR_ARG;
+    iso::Layout lay;
+    lay.size.assign(send_sizes, send_sizes + s);
+    lay.send_displ.assign(send_displs, send_displs + s);
+    lay.recv_displ.assign(recv_displs, recv_displs + s);
+    for (size_t i = 0; i < s; ++i)
+        if (send_sizes[i] != recv_sizes[i]) return ISO_ERR_ARG;      // sizes must match pairwise
+    lay.send_extent = send_extent;
+    lay.recv_extent = recv_extent;
+    lay.slot_major = layout == ISO_LAYOUT_SLOT_MAJOR;
+    int st;
+    if (lay.slot_major) {
+        if ((st = check_planes(lay.size, lay.send_displ, (uint64_t)comm->c.p, false)) != ISO_SUCCESS) return st;
+        if ((st = check_planes(lay.size, lay.recv_displ, (uint64_t)comm->c.p, true)) != ISO_SUCCESS) return st;
+    } else {
+        if ((st = check_rows(lay.size, lay.send_displ, send_extent, false, lay.send_span)) != ISO_SUCCESS) return st;
+        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
+    }
+    return make_request(ISO_OP_ALLTOALL, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm, algorithm, req);
+}
+
+int init_allgatherv(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                    const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent, int layout,
+                    void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm, iso_request_t *req) {
+    if (!req) return ISO_ERR_ARG;
+    *req = nullptr;
+    if (!comm || (layout != ISO_LAYOUT_RANK_MAJOR && layout != ISO_LAYOUT_SLOT_MAJOR)) return ISO_ERR_ARG;
+    const size_t s = (size_t)comm->c.s;
+    if (s && (!recv_sizes || !recv_displs)) return ISO_ERR_ARG;
+    iso::Layout lay;
+    lay.size.assign(s, send_size);
+    lay.send_displ.assign(s, 0);
+    lay.recv_displ.assign(recv_displs, recv_displs + s);
+    for (size_t i = 0; i < s; ++i)
+        if (recv_sizes[i] != send_size) return ISO_ERR_ARG;         // every process sends one size
+    lay.send_extent = send_extent;
+    lay.recv_extent = recv_extent;
+    lay.slot_major = layout == ISO_LAYOUT_SLOT_MAJOR;
+    if (s && send_size > send_extent) return ISO_ERR_ARG;
+    lay.send_span = s ? send_size : 0;
+    int st;
+    if (lay.slot_major) {
+        if ((st = check_planes(lay.size, lay.recv_displ, (uint64_t)comm->c.p, true)) != ISO_SUCCESS) return st;
+    } else {
+        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
+    }
+    return make_request(ISO_OP_ALLGATHER, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm, algorithm, req);
+}
+
 }  // namespace
 
 extern "C" {
@@ -301,24 +376,8 @@ int iso_neighbor_alltoallv_init(const void *sendbuf, const size_t *send_sizes, c
                                 size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                 iso_request_t *req) {
     return guarded([&]() -> int {
-        if (!req) return ISO_ERR_ARG;
-        *req = nullptr;
-        if (!comm) return ISO_ERR_ARG;
-        const size_t s = (size_t)comm->c.s;
-        if (s && (!send_sizes || !send_displs || !recv_sizes || !recv_displs)) return ISO_ERR_ARG;
-        iso::Layout lay;
-        lay.size.assign(send_sizes, send_sizes + s);
-        lay.send_displ.assign(send_displs, send_displs + s);
-        lay.recv_displ.assign(recv_displs, recv_displs + s);
-        for (size_t i = 0; i < s; ++i)
-            if (send_sizes[i] != recv_sizes[i]) return ISO_ERR_ARG;      // sizes must match pairwise
-        lay.send_extent = send_extent;
-        lay.recv_extent = recv_extent;
-        int st;
-        if ((st = check_rows(lay.size, lay.send_displ, send_extent, false, lay.send_span)) != ISO_SUCCESS) return st;
-        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
-        return make_request(ISO_OP_ALLTOALL, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm,
-                            algorithm, req);
+        return init_alltoallv(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes, recv_displs,
+                              recv_extent, ISO_LAYOUT_RANK_MAJOR, workspace, workspace_bytes, comm, algorithm, req);
     });
 }
 
@@ -327,25 +386,29 @@ int iso_neighbor_allgatherv_init(const void *sendbuf, size_t send_size, size_t s
                                  void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
                                  iso_request_t *req) {
     return guarded([&]() -> int {
-        if (!req) return ISO_ERR_ARG;
-        *req = nullptr;
-        if (!comm) return ISO_ERR_ARG;
-        const size_t s = (size_t)comm->c.s;
-        if (s && (!recv_sizes || !recv_displs)) return ISO_ERR_ARG;
-        iso::Layout lay;
-        lay.size.assign(s, send_size);
-        lay.send_displ.assign(s, 0);
-        lay.recv_displ.assign(recv_displs, recv_displs + s);
-        for (size_t i = 0; i < s; ++i)
-            if (recv_sizes[i] != send_size) return ISO_ERR_ARG;         // every process sends one size
-        lay.send_extent = send_extent;
-        lay.recv_extent = recv_extent;
-        if (s && send_size > send_extent) return ISO_ERR_ARG;
-        lay.send_span = s ? send_size : 0;
-        int st;
-        if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
-        return make_request(ISO_OP_ALLGATHER, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm,
-                            algorithm, req);
+        return init_allgatherv(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs, recv_extent,
+                               ISO_LAYOUT_RANK_MAJOR, workspace, workspace_bytes, comm, algorithm, req);
+    });
+}
+
+int iso_neighbor_alltoallv_init_layout(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
+                                       size_t send_extent, void *recvbuf, const size_t *recv_sizes,
+                                       const size_t *recv_displs, size_t recv_extent, int layout,
+                                       void *workspace, size_t workspace_bytes, iso_comm_t comm, int algorithm,
+                                       iso_request_t *req) {
+    return guarded([&]() -> int {
+        return init_alltoallv(sendbuf, send_sizes, send_displs, send_extent, recvbuf, recv_sizes, recv_displs,
+                              recv_extent, layout, workspace, workspace_bytes, comm, algorithm, req);
+    });
+}
+
+int iso_neighbor_allgatherv_init_layout(const void *sendbuf, size_t send_size, size_t send_extent, void *recvbuf,
+                                        const size_t *recv_sizes, const size_t *recv_displs, size_t recv_extent,
+                                        int layout, void *workspace, size_t workspace_bytes, iso_comm_t comm,
+                                        int algorithm, iso_request_t *req) {
+    return guarded([&]() -> int {
+        return init_allgatherv(sendbuf, send_size, send_extent, recvbuf, recv_sizes, recv_displs, recv_extent,
+                               layout, workspace, workspace_bytes, comm, algorithm, req);
     });
 }
 

@@ -51,7 +51,9 @@ struct Layout {
     std::vector<uint64_t> size, send_displ, recv_displ;
     uint64_t send_extent = 0, recv_extent = 0;
     uint64_t send_span = 0, recv_span = 0;    // first to last byte of one rank's blocks
-    bool slot_major = false;                  // regular blocks laid out [s][p][m]: ranks are m bytes apart
+    bool slot_major = false;                  // one plane per neighbour: consecutive ranks' blocks i are
+                                              // size[i] bytes apart (regular blocks: [s][p][m]); the
+                                              // extents then only describe the allgather's send rows
 };
 
 struct Range {
@@ -236,8 +238,18 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
         for (const iso_plan_entry_t &e : r.entries) inf.bytes_read += p * entry_size(e);
     inf.bytes_written = inf.bytes_read;
 
-    const size_t send_len = (inf.delivered_bytes && p) ? (size_t)((p - 1) * lay.send_extent + lay.send_span) : 0;
-    const size_t recv_len = (inf.delivered_bytes && p) ? (size_t)((p - 1) * lay.recv_extent + lay.recv_span) : 0;
+    // bytes from the buffer's start to the end of the last block
+    auto buffer_len = [&](const std::vector<uint64_t> &displ, uint64_t extent, uint64_t span, bool planes) -> size_t {
+        if (!inf.delivered_bytes || !p) return 0;
+        if (!planes) return (size_t)((p - 1) * extent + span);
+        uint64_t end = 0;
+        for (size_t i = 0; i < s; ++i)
+            if (lay.size[i]) end = std::max(end, displ[i] + p * lay.size[i]);
+        return (size_t)end;
+    };
+    const size_t send_len = buffer_len(lay.send_displ, lay.send_extent, lay.send_span,
+                                       lay.slot_major && op == ISO_OP_ALLTOALL);
+    const size_t recv_len = buffer_len(lay.recv_displ, lay.recv_extent, lay.recv_span, lay.slot_major);
     const size_t work_len = inf.delivered_bytes ? (size_t)wl.bytes : 0;
     if (send_len && !sendbuf) return ISO_ERR_ARG;
     if (recv_len && !recvbuf) return ISO_ERR_ARG;
@@ -259,10 +271,10 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     auto place = [&](int buf, int slot, uint64_t &addr, uint64_t &stride) {
         if (buf == ISO_BUF_SEND) {
             addr = (uint64_t)(uintptr_t)sendbuf + (op == ISO_OP_ALLTOALL ? lay.send_displ[(size_t)slot] : lay.send_displ[0]);
-            stride = lay.send_extent;
+            stride = (lay.slot_major && op == ISO_OP_ALLTOALL) ? lay.size[(size_t)slot] : lay.send_extent;
         } else if (buf == ISO_BUF_RECV) {
             addr = (uint64_t)(uintptr_t)recvbuf + lay.recv_displ[(size_t)slot];
-            stride = lay.recv_extent;
+            stride = lay.slot_major ? lay.size[(size_t)slot] : lay.recv_extent;
         } else {
             addr = (uint64_t)(uintptr_t)workspace + wl.offset[(size_t)slot];
             stride = wl.size[(size_t)slot];
@@ -362,23 +374,33 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 l.block.shift_dim = r.kind == ISO_ROUND_SHIFT ? r.dim : -1;
                 for (int j = 0; j < c.d; ++j)
                     if (c.periodic[(size_t)j]) l.block.periodic_mask |= 1u << j;
+                // per launch: k + 1 prefix values, then k multipliers of the divisions by the entries'
+                // unit counts (entry-major order only; the two shifts go into the entry's meta word)
+                const bool entry_major = lay.slot_major;
+                const uint64_t scale = entry_major ? p : 1;    // prefix counts all ranks' units, or one row's
                 uint64_t row_units = 0;
                 prefixes.push_back(0);
                 while (done + k < ents.size()) {
                     const uint64_t next = row_units + ents[done + k].de.units;
                     if (next * p > kMaxUnits) break;
                     row_units = next;
-                    table.push_back(ents[done + k].de);
-                    prefixes.push_back((uint32_t)row_units);
+                    DevEntry de = ents[done + k].de;
+                    const FastDiv by_units = make_fastdiv(de.units);
+                    de.meta |= (by_units.sh1 << 24) | (by_units.sh2 << 25);
+                    table.push_back(de);
+                    prefixes.push_back((uint32_t)(row_units * scale));
                     ++k;
                 }
                 if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
+                for (uint32_t q = 0; q < k; ++q) prefixes.push_back(make_fastdiv(ents[done + q].de.units).mul);
                 total = row_units * p;
                 BlockArgs &b = l.block;
+                b.entry_major = entry_major;
                 b.equal_units = ents[done].de.units;
                 for (uint32_t q = 1; q < k; ++q)
                     if (ents[done + q].de.units != b.equal_units) b.equal_units = 0;
                 b.d_units = make_fastdiv(b.equal_units ? b.equal_units : 1u);
+                b.d_plane = make_fastdiv(b.equal_units ? (uint32_t)(p * b.equal_units) : 1u);
                 b.vector_round = r.kind == ISO_ROUND_VECTOR;
                 b.d_row = make_fastdiv((uint32_t)row_units);
                 const bool shift = r.kind == ISO_ROUND_SHIFT;

@@ -51,7 +51,8 @@ struct alignas(16) DevEntry {
     uint32_t shift;        // SHIFT rounds: residue v; VECTOR rounds: neighbour index
     uint32_t units;        // block launches: block size / unit width of this entry
     uint32_t meta;         // block launches: bits 0-7 log2 of the unit width in bytes;
-                           // bits 8-23 (mesh) dimensions in which R - C^ref must be inside the mesh
+                           // bits 8-23 (mesh) dimensions in which R - C^ref must be inside the mesh;
+                           // bits 24-29 the two shifts of the division by `units` (entry-major order)
     uint32_t ref;          // mesh: neighbour whose coordinates decide whether the move happens
 };
 
@@ -211,7 +212,10 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
 // narrower otherwise, e.g. a 1-byte corner block next to a 16 KiB face block).
 // A rank's units are the concatenation of its entries' units; `prefix[e]` is
 // the first unit of entry e.  The flat index is split into (rank, unit in row),
-// the entry is found by binary search in the prefix array.
+// the entry is found by binary search in the prefix array.  On slot-major
+// buffers (one plane of p blocks per neighbour) the order is (entry, rank, unit)
+// instead: prefix[e] then counts the units of all ranks in the entries before e,
+// and the position inside the plane is divided by the entry's own unit count.
 //
 // MESH (Section 7, non-periodic dimensions): coordinates of non-periodic
 // dimensions are signed and nothing wraps there.  A move happens at rank R only
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
 // C^ref is non-zero); otherwise the destination keeps its content.
 struct BlockArgs {
     const DevEntry *entries;
-    const uint32_t *prefix;    // [k + 1]
+    const uint32_t *prefix;    // [k + 1] first unit of every entry, then [k] multipliers (entry-major order)
     const uint32_t *offsets;   // [s][d] effective coordinates (residues; signed where non-periodic)
     TileMap map;
     uint32_t total;            // p * row_units
@@ -231,7 +235,9 @@ struct BlockArgs {
     uint32_t periodic_mask;    // bit j set: dimension j wraps
     int32_t d;
     uint32_t equal_units;      // != 0: every entry of the launch has this many units (no search)
-    FastDiv d_row, d_inner, d_pj, d_units;
+    uint32_t entry_major;      // slot-major buffers: units ordered (entry, rank, unit) and prefix[e] counts
+                               // the units of all ranks before entry e; else (rank, entry, unit)
+    FastDiv d_row, d_inner, d_pj, d_units, d_plane;   // d_plane: p * equal_units
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
@@ -239,10 +245,10 @@ struct BlockArgs {
 template <bool LDS, bool MESH, bool NTL>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
-    __shared__ uint32_t lds_prefix[LDS ? kLdsEntries + 1 : 1];
+    __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
     const uint32_t *prefix = a.prefix;
     if constexpr (LDS) {
-        if (threadIdx.x <= a.k) lds_prefix[threadIdx.x] = a.prefix[threadIdx.x];
+        for (uint32_t q = threadIdx.x; q <= 2 * a.k; q += kThreads) lds_prefix[q] = a.prefix[q];
         prefix = lds_prefix;
     }
     const EntryTable<LDS> table(a.entries, a.k, lds);     // synchronises the workgroup when LDS
@@ -250,13 +256,16 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     if (!tile_of_block(a.map, tile)) return;
     const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
     if (u >= a.total) return;
-    uint32_t R, w;
-    fast_divmod(u, a.d_row, R, w);
-    uint32_t lo = 0, ch;
-    if (a.equal_units) {                       // equal blocks (a mesh with regular blocks): plain division
-        fast_divmod(w, a.d_units, lo, ch);
+    // flat index -> rank R, entry lo, unit ch of that entry's block
+    uint32_t R = 0, lo = 0, ch = 0, w = u;
+    if (!a.entry_major) fast_divmod(u, a.d_row, R, w);    // w: unit inside the rank's row
+    // entry-major: w counts through the entries one after another, each with the units of all p ranks
+    if (a.k == 1) {
+        ch = w;
+    } else if (a.equal_units) {                            // equal blocks: plain division, no search
+        fast_divmod(w, a.entry_major ? a.d_plane : a.d_units, lo, ch);
     } else {
-        uint32_t hi = a.k;                     // largest e with prefix[e] <= w
+        uint32_t hi = a.k;                                 // largest e with prefix[e] <= w
         while (hi - lo > 1) {
             const uint32_t mid = (lo + hi) >> 1;
             if (prefix[mid] <= w) lo = mid;
@@ -265,6 +274,13 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
         ch = w - prefix[lo];
     }
     const DevEntry en = table[lo];
+    if (a.entry_major) {                                   // ch still counts (rank, unit) inside the plane
+        const FastDiv by_units = a.equal_units
+                                     ? a.d_units
+                                     : FastDiv{prefix[a.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
+        const uint32_t in_plane = ch;
+        fast_divmod(in_plane, by_units, R, ch);
+    }
     uint32_t srcR = R;                                    // modulo 2^32, see vector_source_rank
     if constexpr (MESH) {
         // one pass over the coordinates of R: validity in the masked dimensions, and the source rank

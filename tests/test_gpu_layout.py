@@ -120,3 +120,100 @@ def test_slot_major_named_workloads_full_size(key, m):
                                              cfg.kind)
                 assert torch.equal(recv[i], want), f"{cfg.name} ag plane {i}"
         assert info["vector_bytes"] == 16
+
+
+# ---------------------------------------------------------------- irregular blocks, one plane per neighbour
+
+def _planes(sizes, p, align, gap):
+    """Start of every plane and the total length: plane i holds p blocks of sizes[i] bytes."""
+    displs, at = [], gap
+    for sz in sizes:
+        at = -(-at // align) * align
+        displs.append(at)
+        at += p * sz + gap
+    return displs, at + 3
+
+
+IRREGULAR = [
+    ((4, 3, 5), gen.moore(3, 1), "stencil"),
+    ((6, 5), gen.von_neumann(2, 2), "odd"),
+    ((9, 9, 9), CASES[4][1], "odd"),
+    ((37, 11), gen.moore(2, 2), "stencil"),
+    ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)], "odd"),
+]
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("case", range(len(IRREGULAR)))
+def test_slot_major_irregular_every_byte(case, alg):
+    dims, offsets, flavour = IRREGULAR[case]
+    p, s = int(np.prod(dims)), len(offsets)
+    rng = np.random.default_rng(900 + case)
+    if flavour == "stencil":
+        sizes = [(4096, 64, 16, 1)[i % 4] for i in range(s)]
+        align, gap = 16, 0
+    else:
+        sizes = [int(x) for x in rng.integers(1, 40, size=s)]
+        sizes[s // 2] = 0
+        align, gap = 1, 2
+    rm_displ, ext = gen.packed_displacements(sizes, 1)
+    send_rm = rng.integers(0, 256, size=(p, max(ext, 1)), dtype=np.uint8)
+    want_rm = orc.alltoallv(dims, offsets, send_rm, sizes, rm_displ, np.full_like(send_rm, 0xEE), rm_displ)
+    sd, slen = _planes(sizes, p, align, gap)
+    rd, rlen = _planes(sizes[::-1], p, align, gap + 1)
+    rd = rd[::-1]
+    send_h = np.full(slen, 0x11, np.uint8)
+    want = np.full(rlen, 0xEE, np.uint8)
+    for i, sz in enumerate(sizes):
+        send_h[sd[i]:sd[i] + p * sz] = send_rm[:, rm_displ[i]:rm_displ[i] + sz].reshape(-1)
+        want[rd[i]:rd[i] + p * sz] = want_rm[:, rm_displ[i]:rm_displ[i] + sz].reshape(-1)
+    comm = _comm(dims, offsets)
+    send = torch.from_numpy(send_h).to(DEV)
+    recv = torch.full((rlen,), 0xEE, dtype=torch.uint8, device=DEV)
+    wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+    work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_alltoallv_init_layout(send, sizes, sd, 0, recv, sizes, rd, 0, SM, work, comm, alg)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    iso.iso_request_free(req)
+    assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} {flavour} alg={alg}"
+    assert np.array_equal(send.cpu().numpy(), send_h)
+    # allgather: every rank contributes one block of m bytes, received into s planes
+    m = 48 if flavour == "stencil" else 7
+    one = rng.integers(0, 256, size=(p, m + 3), dtype=np.uint8)
+    gd_rm = [i * m for i in range(s)]
+    wantg_rm = orc.allgatherv(dims, offsets, one, m, np.full((p, max(s * m, 1)), 0xEE, np.uint8), gd_rm)
+    gd, glen = _planes([m] * s, p, align, gap)
+    wantg = np.full(glen, 0xEE, np.uint8)
+    for i in range(s):
+        wantg[gd[i]:gd[i] + p * m] = wantg_rm[:, gd_rm[i]:gd_rm[i] + m].reshape(-1)
+    grecv = torch.full((glen,), 0xEE, dtype=torch.uint8, device=DEV)
+    wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, alg, [m] * s)
+    gwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+    req = iso.iso_neighbor_allgatherv_init_layout(torch.from_numpy(one).to(DEV), m, m + 3, grecv, [m] * s, gd, 0,
+                                                  SM, gwork, comm, alg)
+    iso.iso_start(req)
+    iso.iso_wait(req)
+    iso.iso_request_free(req)
+    assert np.array_equal(grecv.cpu().numpy(), wantg), f"allgather dims={dims} alg={alg}"
+
+
+def test_slot_major_irregular_argument_checks():
+    dims, offsets = (4, 3), gen.moore(2, 1)
+    p, s = 12, 8
+    comm = _comm(dims, offsets)
+    sizes = [16] * s
+    d, n = _planes(sizes, p, 16, 0)
+    buf = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    out = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    work = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    clash = list(d)
+    clash[1] = d[0] + 16                      # plane 1 starts inside plane 0
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoallv_init_layout(buf, sizes, d, 0, out, sizes, clash, 0, SM, work, comm)
+    assert e.value.status == iso.ISO_ERR_OVERLAP
+    req = iso.iso_neighbor_alltoallv_init_layout(buf, sizes, clash, 0, out, sizes, d, 0, SM, work, comm)  # send may
+    iso.iso_request_free(req)
+    with pytest.raises(iso.IsoError) as e:      # sizes must match pairwise, whatever the layout
+        iso.iso_neighbor_alltoallv_init_layout(buf, sizes, d, 0, out, [16] * (s - 1) + [32], d, 0, SM, work, comm)
+    assert e.value.status == iso.ISO_ERR_ARG
