@@ -86,6 +86,30 @@ int main() {
                 CK(hipMemcpy(got.data(), recv_d, recv_bytes, hipMemcpyDeviceToHost));
                 REQUIRE(memcmp(got.data(), want.data(), recv_bytes) == 0);
                 REQUIRE(iso_request_free(&rq) == ISO_SUCCESS && rq == nullptr);
+                // the same collective on slot-major buffers: [s][p][m] instead of [p][s][m]
+                if (recv_bytes) {
+                    std::vector<uint8_t> send_sm(send_bytes + 1), want_sm(recv_bytes + 1), got_sm(recv_bytes + 1);
+                    for (int64_t R = 0; R < p; ++R)
+                        for (int i = 0; i < s; ++i) {
+                            if (op == 0) memcpy(&send_sm[((size_t)i * p + R) * m], &send_h[((size_t)R * s + i) * m], m);
+                            memcpy(&want_sm[((size_t)i * p + R) * m], &want[((size_t)R * s + i) * m], m);
+                        }
+                    if (op == 1) send_sm = send_h;
+                    uint8_t *ssm_d, *rsm_d; CK(hipMalloc(&ssm_d, send_bytes + 16)); CK(hipMalloc(&rsm_d, recv_bytes + 16));
+                    CK(hipMemcpy(ssm_d, send_sm.data(), send_bytes, hipMemcpyHostToDevice));
+                    CK(hipMemset(rsm_d, 0xEE, recv_bytes + 16));
+                    REQUIRE((op == 0 ? iso_neighbor_alltoall_init_layout : iso_neighbor_allgather_init_layout)(
+                                ssm_d, rsm_d, m, ISO_LAYOUT_SLOT_MAJOR, work_d, wsb, comm, alg, &rq) == ISO_SUCCESS);
+                    REQUIRE(iso_start(rq, st) == ISO_SUCCESS);
+                    REQUIRE(iso_wait(rq) == ISO_SUCCESS);
+                    CK(hipMemcpy(got_sm.data(), rsm_d, recv_bytes, hipMemcpyDeviceToHost));
+                    REQUIRE(memcmp(got_sm.data(), want_sm.data(), recv_bytes) == 0);
+                    REQUIRE(iso_request_free(&rq) == ISO_SUCCESS);
+                    REQUIRE((op == 0 ? iso_neighbor_alltoall_init_layout : iso_neighbor_allgather_init_layout)(
+                                ssm_d, rsm_d, m, 5, work_d, wsb, comm, alg, &rq) == ISO_ERR_ARG);
+                    CK(hipFree(ssm_d)); CK(hipFree(rsm_d));
+                    ++runs;
+                }
                 CK(hipFree(work_d));
                 ++runs;
             }
