@@ -136,36 +136,55 @@ __device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t p
     return rj >= v ? -(int64_t)v : (int64_t)(pj - v);
 }
 
-// Source rank of R for a move by the full offset vector c[0..d): R (-) c on the torus.
-// Up to kUnrolledDims dimensions the loop over the dimensions is unrolled, so that the
-// per-dimension launch constants are read at fixed kernel-argument offsets (scalar
-// registers) and the d loads of c are issued together; indexing those arrays with a
-// run-time j costs a dependent scalar load per dimension and, at one unit per lane, a
-// third of the kernel's throughput.
+// Coordinate decodes over all dimensions.  For d <= kUnrolledDims the code is instantiated
+// for the exact d (one uniform switch, then straight-line code): the per-dimension launch
+// constants are then read at fixed kernel-argument offsets (scalar registers) and the loads
+// of the offset vector are issued together.  Indexing those arrays with a run-time j costs a
+// dependent scalar load and several uniform branches per dimension, and at one unit per lane
+// that is a third of the kernel's throughput.
+// Rank arithmetic is done modulo 2^32: ranks are below 2^31 and every true result lies in
+// [0, p), so wrapped intermediate values are harmless.
 constexpr int kUnrolledDims = 6;
 
-// Rank arithmetic is done modulo 2^32: ranks are below 2^31 and every true result lies in
-// [0, p), so the wrapped intermediate values are harmless.
-__device__ __forceinline__ uint32_t vector_source_rank(uint32_t R, const uint32_t *__restrict__ c, int32_t d,
-                                                       const FastDiv (&d_dims)[ISO_MAX_DIMS],
-                                                       const uint32_t (&inner)[ISO_MAX_DIMS]) {
+// Source rank of R for a move by the full offset vector c[0..d): R (-) c on the torus.
+template <int D>
+__device__ __forceinline__ uint32_t vector_source_rank_d(uint32_t R, const uint32_t *__restrict__ c,
+                                                         const FastDiv (&d_dims)[ISO_MAX_DIMS],
+                                                         const uint32_t (&inner)[ISO_MAX_DIMS]) {
+    uint32_t cj[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) cj[j] = c[j];
     uint32_t srcR = R, rem = R;
-    auto step = [&](int j, uint32_t cj) {
+#pragma unroll
+    for (int j = D - 1; j >= 0; --j) {
         uint32_t q, rj;
         fast_divmod(rem, d_dims[j], q, rj);
         rem = q;
-        srcR -= cj * inner[j];                                   // cj steps back ...
-        if (rj < cj) srcR += d_dims[j].div * inner[j];           // ... around the ring
-    };
-    if (d <= kUnrolledDims) {
-        uint32_t cj[kUnrolledDims];
-#pragma unroll
-        for (int j = 0; j < kUnrolledDims; ++j) cj[j] = j < d ? c[j] : 0u;
-#pragma unroll
-        for (int j = kUnrolledDims - 1; j >= 0; --j)
-            if (j < d) step(j, cj[j]);
-    } else {
-        for (int j = d - 1; j >= 0; --j) step(j, c[j]);
+        srcR -= cj[j] * inner[j];                                   // cj steps back ...
+        if (rj < cj[j]) srcR += d_dims[j].div * inner[j];           // ... around the ring
+    }
+    return srcR;
+}
+
+__device__ __forceinline__ uint32_t vector_source_rank(uint32_t R, const uint32_t *__restrict__ c, int32_t d,
+                                                       const FastDiv (&d_dims)[ISO_MAX_DIMS],
+                                                       const uint32_t (&inner)[ISO_MAX_DIMS]) {
+    switch (d) {
+        case 1: return vector_source_rank_d<1>(R, c, d_dims, inner);
+        case 2: return vector_source_rank_d<2>(R, c, d_dims, inner);
+        case 3: return vector_source_rank_d<3>(R, c, d_dims, inner);
+        case 4: return vector_source_rank_d<4>(R, c, d_dims, inner);
+        case 5: return vector_source_rank_d<5>(R, c, d_dims, inner);
+        case 6: return vector_source_rank_d<6>(R, c, d_dims, inner);
+        default: break;
+    }
+    uint32_t srcR = R, rem = R;
+    for (int j = d - 1; j >= 0; --j) {
+        uint32_t q, rj;
+        fast_divmod(rem, d_dims[j], q, rj);
+        rem = q;
+        srcR -= c[j] * inner[j];
+        if (rj < c[j]) srcR += d_dims[j].div * inner[j];
     }
     return srcR;
 }
@@ -242,6 +261,83 @@ struct BlockArgs {
     uint32_t inner_of[ISO_MAX_DIMS];
 };
 
+// Mesh: does the move of entry `en` happen at rank R (R - C^ref inside the mesh in every masked
+// dimension), and from which rank?  Offsets of non-periodic dimensions are signed values stored
+// as two's complement, so one unsigned comparison tests both ends of the dimension.
+template <int D>
+__device__ __forceinline__ bool mesh_source_rank_d(const BlockArgs &a, const DevEntry &en, uint32_t R,
+                                                   uint32_t &srcR) {
+    const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
+    const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
+    uint32_t cr[D], r[D];
+#pragma unroll
+    for (int j = 0; j < D; ++j) cr[j] = cref[j];
+    uint32_t rem = R;
+#pragma unroll
+    for (int j = D - 1; j >= 0; --j) {
+        uint32_t q;
+        fast_divmod(rem, a.d_dims[j], q, r[j]);
+        rem = q;
+    }
+    uint32_t outside = 0;
+#pragma unroll
+    for (int j = 0; j < D; ++j)
+        outside |= ((mask >> j) & 1u) & (uint32_t)((uint32_t)(r[j] - cr[j]) >= a.d_dims[j].div);
+    if (outside) return false;
+    srcR = R;
+    if (a.vector_round) {                                  // en.shift: the neighbour whose offsets move the block
+        const uint32_t *cvec = a.offsets + (size_t)en.shift * a.d;
+        uint32_t cv[D];
+#pragma unroll
+        for (int j = 0; j < D; ++j) cv[j] = cvec[j];
+#pragma unroll
+        for (int j = 0; j < D; ++j) {
+            srcR -= cv[j] * a.inner_of[j];                 // signed where the dimension does not wrap
+            if (((a.periodic_mask >> j) & 1u) && r[j] < cv[j]) srcR += a.d_dims[j].div * a.inner_of[j];
+        }
+    } else if (a.shift_dim >= 0) {                         // en.shift: the distance along the one moving dimension
+        const uint32_t q = fast_div(R, a.d_inner);
+        const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
+        srcR -= en.shift * a.inner;
+        if (((a.periodic_mask >> a.shift_dim) & 1u) && rj < en.shift) srcR += a.pj * a.inner;
+    }
+    return true;
+}
+
+__device__ __forceinline__ bool mesh_source_rank(const BlockArgs &a, const DevEntry &en, uint32_t R,
+                                                 uint32_t &srcR) {
+    switch (a.d) {
+        case 1: return mesh_source_rank_d<1>(a, en, R, srcR);
+        case 2: return mesh_source_rank_d<2>(a, en, R, srcR);
+        case 3: return mesh_source_rank_d<3>(a, en, R, srcR);
+        case 4: return mesh_source_rank_d<4>(a, en, R, srcR);
+        case 5: return mesh_source_rank_d<5>(a, en, R, srcR);
+        case 6: return mesh_source_rank_d<6>(a, en, R, srcR);
+        default: break;
+    }
+    // more dimensions: one pass with run-time indices
+    const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
+    const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
+    // in shift rounds en.shift is the distance itself: no row of the offset table is addressed with it
+    const uint32_t *cvec = a.vector_round ? a.offsets + (size_t)en.shift * a.d : cref;
+    uint32_t rem = R;
+    bool has_source = true;
+    srcR = R;
+    for (int j = a.d - 1; j >= 0; --j) {
+        uint32_t q, rj;
+        fast_divmod(rem, a.d_dims[j], q, rj);
+        rem = q;
+        const uint32_t pj = a.d_dims[j].div;
+        if (((mask >> j) & 1u) && (uint32_t)(rj - cref[j]) >= pj) has_source = false;
+        if (a.vector_round || j == a.shift_dim) {
+            const uint32_t cj = a.vector_round ? cvec[j] : en.shift;
+            srcR -= cj * a.inner_of[j];
+            if (((a.periodic_mask >> j) & 1u) && rj < cj) srcR += pj * a.inner_of[j];
+        }
+    }
+    return has_source;
+}
+
 template <bool LDS, bool MESH, bool NTL>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
@@ -283,43 +379,7 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     }
     uint32_t srcR = R;                                    // modulo 2^32, see vector_source_rank
     if constexpr (MESH) {
-        // one pass over the coordinates of R: validity in the masked dimensions, and the source rank
-        const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
-        const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
-        // vector rounds: en.shift is the neighbour whose offsets move the block; in shift rounds it is
-        // the distance itself, so no row of the offset table may be addressed with it
-        const uint32_t *cvec = a.vector_round ? a.offsets + (size_t)en.shift * a.d : cref;
-        uint32_t rem = R;
-        bool has_source = true;
-        auto step = [&](int j, uint32_t cref_j, uint32_t cvec_j) {
-            uint32_t q, rj;
-            fast_divmod(rem, a.d_dims[j], q, rj);
-            rem = q;
-            const uint32_t pj = a.d_dims[j].div;
-            if ((mask >> j) & 1u) {
-                const int64_t t = (int64_t)rj - (int64_t)(int32_t)cref_j;
-                if (t < 0 || t >= (int64_t)pj) has_source = false;
-            }
-            if (a.vector_round || j == a.shift_dim) {
-                const uint32_t cj = a.vector_round ? cvec_j : en.shift;
-                srcR -= cj * a.inner_of[j];               // signed where the dimension does not wrap
-                if (((a.periodic_mask >> j) & 1u) && rj < cj) srcR += pj * a.inner_of[j];
-            }
-        };
-        if (a.d <= kUnrolledDims) {
-            uint32_t cr[kUnrolledDims], cv[kUnrolledDims];
-#pragma unroll
-            for (int j = 0; j < kUnrolledDims; ++j) {
-                cr[j] = j < a.d ? cref[j] : 0u;
-                cv[j] = j < a.d ? cvec[j] : 0u;
-            }
-#pragma unroll
-            for (int j = kUnrolledDims - 1; j >= 0; --j)
-                if (j < a.d) step(j, cr[j], cv[j]);
-        } else {
-            for (int j = a.d - 1; j >= 0; --j) step(j, cref[j], cvec[j]);
-        }
-        if (!has_source) return;                          // leave the destination as it is
+        if (!mesh_source_rank(a, en, R, srcR)) return;    // no source: leave the destination as it is
     } else if (a.vector_round) {
         srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner_of);
     } else {
