@@ -217,3 +217,30 @@ def test_slot_major_irregular_argument_checks():
     with pytest.raises(iso.IsoError) as e:      # sizes must match pairwise, whatever the layout
         iso.iso_neighbor_alltoallv_init_layout(buf, sizes, d, 0, out, [16] * (s - 1) + [32], d, 0, SM, work, comm)
     assert e.value.status == iso.ISO_ERR_ARG
+
+
+def test_slot_major_irregular_on_a_mesh():
+    dims, periodic, offsets = (9, 7, 5), (0, 0, 1), gen.moore(3, 1)
+    p, s = 315, 26
+    sizes = gen.stencil_block_sizes(offsets, 16)              # 256 / 16 / 1 bytes
+    sd, n = _planes(sizes, p, 16, 0)
+    rng = np.random.default_rng(31)
+    send_h = rng.integers(0, 256, size=n, dtype=np.uint8)
+    src, valid = orc.source_ranks_mesh(dims, periodic, offsets)
+    want = np.full(n, 0xEE, np.uint8)
+    for i, sz in enumerate(sizes):
+        plane_in = send_h[sd[i]:sd[i] + p * sz].reshape(p, sz)
+        plane_out = want[sd[i]:sd[i] + p * sz].reshape(p, sz)
+        v = valid[:, i]
+        plane_out[v] = plane_in[src[v, i]]
+    comm = _comm(dims, offsets, periodic)
+    send = torch.from_numpy(send_h).to(DEV)
+    for alg in ALGS[:4]:
+        recv = torch.full((n,), 0xEE, dtype=torch.uint8, device=DEV)
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+        work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoallv_init_layout(send, sizes, sd, 0, recv, sizes, sd, 0, SM, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        iso.iso_request_free(req)
+        assert np.array_equal(recv.cpu().numpy(), want), ALG_NAMES[alg]
