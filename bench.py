@@ -424,6 +424,22 @@ def main():
                       f"median; C twin of the oracle, OpenMP over ranks",
             "ms_per_step": round(t_med * 1e3, 3),
         }
+        # the same oracle on one thread, and (small workloads only) its numpy form
+        t1 = []
+        for _ in range(3):
+            t = time.perf_counter()
+            for op in ops:
+                fn = c_twin.alltoall if op == iso.ISO_OP_ALLTOALL else c_twin.allgather
+                fn(cfg.dims, cfg.offsets, host[op], out=outs[op], threads=1)
+            t1.append(time.perf_counter() - t)
+            if sum(t1) > args.cpu_seconds:
+                break
+        out["cpu_baseline"]["one_thread_GBs"] = round(delivered / median(t1) / 1e9, 3)
+        if delivered <= (1 << 29):
+            t = time.perf_counter()
+            for op in ops:
+                (orc.alltoall if op == iso.ISO_OP_ALLTOALL else orc.allgather)(cfg.dims, cfg.offsets, host[op])
+            out["cpu_baseline"]["numpy_oracle_GBs"] = round(delivered / (time.perf_counter() - t) / 1e9, 3)
 
     for r in reqs:
         iso.iso_request_free(r)
