@@ -68,7 +68,8 @@ enum iso_algorithm {
      * round moves blocks one hop along one dimension; per dimension max c_j
      * positive steps, then max -c_j negative steps, counted on the coordinates
      * as given (not reduced modulo p_j).  D = sum_j (max+ + max-) launches,
-     * V = sum_i ||C^i||_1 block-moves per rank (all-to-all), W (allgather). */
+     * V = sum_i ||C^i||_1 block-moves per rank (all-to-all), W (allgather).
+     * ISO_ERR_TOO_LARGE if D would exceed 65536. */
     ISO_ALG_ONEHOP         = 4
 };
 

@@ -17,6 +17,8 @@
 
 namespace iso {
 
+constexpr int64_t kMaxOneHopRounds = 1 << 16;
+
 int Comm::nnz(int i) const {
     int n = 0;
     for (int j = 0; j < d; ++j) n += c(i, j) != 0;
@@ -526,13 +528,27 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
             else
                 plan_allgather_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
             break;
-        case ISO_ALG_ONEHOP:
+        case ISO_ALG_ONEHOP: {
             if (c.mesh) return ISO_ERR_ARG;
+            // one launch per unit of coordinate: refuse neighbourhoods whose raw coordinates
+            // would need an absurd number of them (and keep the hop arithmetic inside int32)
+            int64_t steps = 0;
+            for (int j = 0; j < c.d; ++j) {
+                int64_t up = 0, down = 0;
+                for (int i = 0; i < c.s; ++i) {
+                    const int64_t v = c.raw[(size_t)i * c.d + j];
+                    up = std::max(up, v);
+                    down = std::max(down, -v);
+                }
+                steps += up + down;
+            }
+            if (steps > kMaxOneHopRounds) return ISO_ERR_TOO_LARGE;
             if (op == ISO_OP_ALLTOALL)
                 plan_alltoall_onehop(c, pl);
             else
                 plan_allgather_onehop(c, pl);
             break;
+        }
         case ISO_ALG_SX_ROUNDS:
         case ISO_ALG_SX_FUSED:
             plan_s_exchange(c, op, algorithm == ISO_ALG_SX_FUSED, pl);

@@ -2,6 +2,7 @@
 // UndefinedBehaviorSanitizer and pushes seeded random neighbourhoods through every
 // algorithm.  Checks structural invariants only (results are checked elsewhere);
 // the point is that the sanitizers see every code path.  Prints the number of plans.
+#include <climits>
 #include <cstdint>
 #include <cstdio>
 #include <cstdlib>
@@ -64,6 +65,34 @@ int main() {
                 }
                 REQUIRE((int)final_writes.size() == s);
             }
+    }
+    // arguments that must be refused, never crash
+    {
+        iso::Comm c;
+        int32_t one[1] = {4}, zero[1] = {0}, neg[2] = {3, -2}, big[3] = {2048, 2048, 1024}, off[1] = {1};
+        int32_t many[ISO_MAX_DIMS + 1];
+        for (auto &x : many) x = 1;
+        REQUIRE(iso::build_comm(0, one, nullptr, 0, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(ISO_MAX_DIMS + 1, many, nullptr, 0, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(1, nullptr, nullptr, 0, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(1, zero, nullptr, 0, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(2, neg, nullptr, 0, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(1, one, nullptr, -1, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(1, one, nullptr, 1, nullptr, c) == ISO_ERR_ARG);
+        REQUIRE(iso::build_comm(3, big, nullptr, 0, nullptr, c) == ISO_ERR_TOO_LARGE);      // 2^32 processes
+        REQUIRE(iso::build_comm(ISO_MAX_DIMS, many, nullptr, 0, nullptr, c) == ISO_SUCCESS);
+        REQUIRE(iso::build_comm(1, one, nullptr, 1, off, c) == ISO_SUCCESS);
+        iso::Plan pl;
+        REQUIRE(iso::build_plan(c, 2, ISO_ALG_COMBINED, pl) == ISO_ERR_ARG);
+        REQUIRE(iso::build_plan(c, ISO_OP_ALLTOALL, 99, pl) == ISO_ERR_ARG);
+        // extreme offsets: the reduction modulo the dimension size must not overflow
+        int32_t dims2[2] = {7, 5}, ext[4] = {INT32_MAX, INT32_MIN, INT32_MIN, INT32_MAX};
+        REQUIRE(iso::build_comm(2, dims2, nullptr, 2, ext, c) == ISO_SUCCESS);
+        for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < 2; ++j) REQUIRE(c.c(i, j) >= 0 && c.c(i, j) < dims2[j]);
+        for (int alg = 0; alg <= ISO_ALG_ONEHOP; ++alg)   // one hop per unit of coordinate would be 2^32 rounds
+            for (int op = 0; op < 2; ++op)
+                REQUIRE(iso::build_plan(c, op, alg, pl) == (alg == ISO_ALG_ONEHOP ? ISO_ERR_TOO_LARGE : ISO_SUCCESS));
     }
     std::printf("%ld\n", plans);
     return 0;
