@@ -51,6 +51,18 @@ int guarded(F &&f) {
     }
 }
 
+// p times the sum of the block sizes must stay far inside 64 bits (all later address and
+// workspace arithmetic relies on it).
+bool sizes_too_large(const iso::Comm &c, const std::vector<uint64_t> &sizes) {
+    const uint64_t limit = (~uint64_t(0) >> 2) / (uint64_t)std::max<int64_t>(1, c.p);
+    uint64_t sum = 0;
+    for (uint64_t sz : sizes) {
+        if (sz > limit || sum > limit - sz) return true;
+        sum += sz;
+    }
+    return false;
+}
+
 // Regular blocks of m bytes.  Rank-major: a process's s blocks back to back in neighbour
 // order, [p][s][m].  Slot-major: one plane of p blocks per neighbour, [s][p][m]; the
 // distance between consecutive ranks is then m and block i starts i*p*m into the buffer.
@@ -316,6 +328,7 @@ int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t
         iso::Plan pl;
         int st = iso::build_plan(comm->c, op, algorithm, pl);
         if (st != ISO_SUCCESS) return st;
+        if (sizes_too_large(comm->c, std::vector<uint64_t>((size_t)comm->c.s, m))) return ISO_ERR_TOO_LARGE;
         *bytes = (size_t)iso::work_layout(pl, regular_layout(comm->c, op, m)).bytes;
         return ISO_SUCCESS;
     });
@@ -329,6 +342,7 @@ int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *
         if (st != ISO_SUCCESS) return st;
         iso::Layout lay;
         lay.size.assign(sizes, sizes + comm->c.s);
+        if (sizes_too_large(comm->c, lay.size)) return ISO_ERR_TOO_LARGE;
         *bytes = (size_t)iso::work_layout(pl, lay).bytes;
         return ISO_SUCCESS;
     });

@@ -479,3 +479,21 @@ def test_random_mesh_plans_reach_the_oracle_result(seed):
             got = _replay_mesh(dims, periodic, offsets, op, order, _plan_rounds(plan), pinfo["work_slots"],
                                send, m)
             assert np.array_equal(got, want), (dims, periodic, offsets, alg, op)
+
+
+def test_sizes_that_would_overflow_are_refused():
+    comm = iso.iso_neighborhood_create((32, 32, 32), gen.moore(3, 1))
+    for alg in ALGS:
+        with pytest.raises(iso.IsoError) as e:
+            iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, 1 << 62)
+        assert e.value.status == iso.ISO_ERR_TOO_LARGE
+        with pytest.raises(iso.IsoError) as e:
+            iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, alg, [1 << 61] * 26)
+        assert e.value.status == iso.ISO_ERR_TOO_LARGE
+    assert iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, 256) == 20 * 32768 * 256
+    # the one-hop schedule needs one launch per unit of coordinate: absurd counts are refused
+    far = iso.iso_neighborhood_create((5, 5), [(70000, 0), (0, -1)])
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_plan_create(far, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_ONEHOP)
+    assert e.value.status == iso.ISO_ERR_TOO_LARGE
+    assert iso.iso_plan_info(iso.iso_plan_create(far, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED))["launches"] == 2   # a same-rank copy (70000 = 0 mod 5) and one shift
