@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparison algorithms and the copy ceiling")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--small-sweep", action="store_true",
+                    help="instead of the benchmark: all-to-all on tori of about 500 processes (the paper's own "
+                         "regime, Section 4), every algorithm, three block sizes; prints one JSON line")
     return ap.parse_args()
 
 
@@ -60,6 +63,52 @@ def median(xs):
     return xs[n // 2] if n % 2 else 0.5 * (xs[n // 2 - 1] + xs[n // 2])
 
 
+def small_sweep():
+    """Section 4's setting carried over: Moore neighbourhoods on tori of about 500 processes,
+    block sizes from a few bytes to 2 KiB.  Here every size is bound by the per-launch cost, the
+    GPU's counterpart of the message start-up latency, so the time follows the number of launches:
+    D for the message-combining schedules, s for the straightforward algorithm."""
+    import numpy as np
+    import torch
+    import iso_inputs as gen
+    import paper_1606_07676_amd as iso
+    iso.load_library()
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    algs = (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
+            ("onehop", iso.ISO_ALG_ONEHOP), ("sx_rounds", iso.ISO_ALG_SX_ROUNDS), ("sx_fused", iso.ISO_ALG_SX_FUSED))
+    cases = (("moore_d2_r1", (30, 16), gen.moore(2, 1)), ("moore_d3_r1", (8, 8, 8), gen.moore(3, 1)),
+             ("moore_d4_r1", (6, 5, 4, 4), gen.moore(4, 1)), ("moore_d5_r1", (4,) * 5, gen.moore(5, 1)),
+             ("moore_d3_r3", (8, 8, 8), gen.moore(3, 3)))
+    rows = []
+    for name, dims, offs in cases:
+        p, s = int(np.prod(dims)), len(offs)
+        comm = iso.iso_neighborhood_create(dims, offs)
+        for m in (16, 256, 2048):
+            send = gen.alltoall_send_torch(1, p, s, m, device=dev)
+            recv = torch.empty((p, s, m), dtype=torch.uint8, device=dev)
+            row = {"neighbourhood": name, "dims": list(dims), "p": p, "s": s, "m": m}
+            for an, alg in algs:
+                wsb = iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, m)
+                work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+                req = iso.iso_neighbor_alltoall_init(send, recv, m, work, comm, alg)
+                for _ in range(10):
+                    iso.iso_start(req, stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(200):
+                    iso.iso_start(req, stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                row[an] = {"us": round(e0.elapsed_time(e1) / 200 * 1e3, 2),
+                           "launches": iso.iso_request_info(req)["launches"]}
+                iso.iso_request_free(req)
+            log(row)
+            rows.append(row)
+    print(json.dumps({"small_sweep": rows}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -75,6 +124,9 @@ def main():
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible")
         sys.exit(1)
+    if args.small_sweep:
+        small_sweep()
+        return
     iso.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
