@@ -296,6 +296,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             if (he.size == 0) continue;                       // empty blocks make no move
             place(pe.src_buf, pe.src_slot, he.de.src, he.de.src_stride);
             place(pe.dst_buf, pe.dst_slot, he.de.dst, he.de.dst_stride);
+            // the kernels multiply a rank by a 32-bit stride
+            if ((he.de.src_stride | he.de.dst_stride) >> 32) return ISO_ERR_TOO_LARGE;
             he.de.shift = r.kind == ISO_ROUND_VECTOR ? (uint32_t)pe.neighbor : (uint32_t)pe.shift;
             const uint32_t l2 = unit_log2_of({he.size, he.de.src, he.de.dst, he.de.src_stride, he.de.dst_stride});
             const uint64_t units = he.size >> l2;

@@ -46,8 +46,8 @@ constexpr uint32_t kLdsEntries = 128;   // rounds with at most this many entries
 struct alignas(16) DevEntry {
     uint64_t src;          // address of rank 0's source block
     uint64_t dst;          // address of rank 0's destination block
-    uint64_t src_stride;   // bytes between consecutive ranks in the source buffer
-    uint64_t dst_stride;
+    uint64_t src_stride;   // bytes between consecutive ranks in the source buffer; below 2^32 (checked
+    uint64_t dst_stride;   // when the request is bound), so that rank * stride + base is one 32x32+64 multiply-add
     uint32_t shift;        // SHIFT rounds: residue v; VECTOR rounds: neighbour index
     uint32_t units;        // block launches: block size / unit width of this entry
     uint32_t meta;         // block launches: bits 0-7 log2 of the unit width in bytes;
@@ -114,6 +114,11 @@ __device__ __forceinline__ void move_unit(uint64_t dst, uint64_t src, uint32_t c
     __builtin_nontemporal_store(v, (dst_ptr)dst + ch);
 }
 
+// Address of rank R's block: base + R * stride with the stride known to fit 32 bits.
+__device__ __forceinline__ uint64_t block_address(uint64_t base, uint32_t R, uint64_t stride) {
+    return base + (uint64_t)R * (uint32_t)stride;
+}
+
 // Entry table of the launch: from LDS (staged once per workgroup) when it fits,
 // else straight from global memory (cached).
 template <bool LDS>
@@ -130,11 +135,6 @@ struct EntryTable {
     }
     __device__ __forceinline__ DevEntry operator[](uint32_t e) const { return tab[e]; }
 };
-
-// steps back along a periodic dimension of size pj by residue v, from coordinate rj
-__device__ __forceinline__ int64_t wrap_back(uint32_t rj, uint32_t v, uint32_t pj) {
-    return rj >= v ? -(int64_t)v : (int64_t)(pj - v);
-}
 
 // Coordinate decodes over all dimensions.  For d <= kUnrolledDims the code is instantiated
 // for the exact d (one uniform switch, then straight-line code): the per-dimension launch
@@ -205,8 +205,11 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
     const DevEntry en = table[e];
     // v steps back along the dimension, with wrap-around
-    const uint64_t srcR = (uint64_t)((int64_t)R + wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner);
-    move_unit<V, NTL>(en.dst + (uint64_t)R * en.dst_stride, en.src + srcR * en.src_stride, ch);
+    // v steps back along the dimension, around the ring where that passes coordinate 0 (modulo 2^32;
+    // the true result lies in [0, p))
+    uint32_t srcR = R - en.shift * a.inner;
+    if (rj < en.shift) srcR += a.pj * a.inner;
+    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
 }
 
 template <typename V, bool LDS>
@@ -223,7 +226,7 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
     else fast_divmod(t, a.d_k, R, e);
     const DevEntry en = table[e];
     const uint32_t srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner);
-    move_unit<V, false>(en.dst + (uint64_t)R * en.dst_stride, en.src + (uint64_t)srcR * en.src_stride, ch);
+    move_unit<V, false>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
 }
 
 // Irregular blocks (the v/w interfaces of Section 2): every entry has its own
@@ -385,10 +388,11 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     } else {
         const uint32_t q = fast_div(R, a.d_inner);
         const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
-        srcR = (uint32_t)((int64_t)R + wrap_back(rj, en.shift, a.pj) * (int64_t)a.inner);
+        srcR -= en.shift * a.inner;
+        if (rj < en.shift) srcR += a.pj * a.inner;
     }
-    const uint64_t src = en.src + (uint64_t)srcR * en.src_stride;
-    const uint64_t dst = en.dst + (uint64_t)R * en.dst_stride;
+    const uint64_t src = block_address(en.src, srcR, en.src_stride);
+    const uint64_t dst = block_address(en.dst, R, en.dst_stride);
     switch (en.meta & 0xFFu) {
         case 4: move_unit<vec16_t, NTL>(dst, src, ch); break;
         case 3: move_unit<vec8_t, false>(dst, src, ch); break;
