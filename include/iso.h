@@ -209,7 +209,8 @@ int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t
  * The three ranges must not overlap (ISO_ERR_OVERLAP); in-place operation is
  * not supported.  Each must lie inside one device allocation (ISO_ERR_POINTER).
  * ISO_ERR_TOO_LARGE if p*m >= 2^36 (one block plane would exceed what a launch
- * indexes).  The buffers are bound to the request; iso_start may be called any
+ * indexes) or if consecutive ranks' blocks are 2^32 bytes or more apart (s*m here,
+ * an extent in the irregular calls).  The buffers are bound to the request; iso_start may be called any
  * number of times.  Needs a GPU (uploads the index maps: one hipMalloc + one
  * synchronous hipMemcpy). */
 int iso_neighbor_alltoall_init(const void *sendbuf, void *recvbuf, size_t m,
