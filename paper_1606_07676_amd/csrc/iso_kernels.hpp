@@ -299,8 +299,10 @@ __device__ __forceinline__ bool mesh_source_rank_d(const BlockArgs &a, const Dev
             if (((a.periodic_mask >> j) & 1u) && r[j] < cv[j]) srcR += a.d_dims[j].div * a.inner_of[j];
         }
     } else if (a.shift_dim >= 0) {                         // en.shift: the distance along the one moving dimension
-        const uint32_t q = fast_div(R, a.d_inner);
-        const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
+        uint32_t rj = 0;
+#pragma unroll
+        for (int j = 0; j < D; ++j)
+            if (j == a.shift_dim) rj = r[j];                // uniform condition: a select, not a branch per lane
         srcR -= en.shift * a.inner;
         if (((a.periodic_mask >> a.shift_dim) & 1u) && rj < en.shift) srcR += a.pj * a.inner;
     }
