@@ -31,7 +31,7 @@ constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per laun
         }                                              \
     } while (0)
 
-enum LaunchKernel { kShiftKernel = 0, kVectorKernel = 1, kBlockKernel = 2 };
+enum LaunchKernel { kShiftKernel = 0, kVectorKernel = 1, kBlockKernel = 2, kMeshShiftKernel = 3 };
 
 struct Launch {
     int kernel;            // LaunchKernel
@@ -43,6 +43,7 @@ struct Launch {
     ShiftArgs shift;
     VectorArgs vec;
     BlockArgs block;
+    MeshArgs mesh_shift;
 };
 
 // Sizes and displacements (bytes) of the s blocks inside one rank's send and
@@ -130,7 +131,10 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k) {
     while (run_log2 > 0 && (8u << run_log2) > n_tiles) --run_log2;
     const uint32_t span = 8u << run_log2;
     l.grid = (uint32_t)((((uint64_t)n_tiles + span - 1) / span) * span);
-    TileMap &tm = l.kernel == kVectorKernel ? l.vec.map : l.kernel == kBlockKernel ? l.block.map : l.shift.map;
+    TileMap &tm = l.kernel == kVectorKernel  ? l.vec.map
+                  : l.kernel == kBlockKernel ? l.block.map
+                  : l.kernel == kMeshShiftKernel ? l.mesh_shift.map
+                                                 : l.shift.map;
     tm.n_tiles = n_tiles;
     tm.run_log2 = run_log2;
     l.lds_table = k <= kLdsEntries;
@@ -140,6 +144,9 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k) {
     } else if (l.kernel == kBlockKernel) {
         l.block.total = total;
         l.block.k = k;
+    } else if (l.kernel == kMeshShiftKernel) {
+        l.mesh_shift.total = total;
+        l.mesh_shift.k = k;
     } else {
         l.shift.total = total;
         l.shift.k = k;
@@ -153,6 +160,16 @@ void enqueue_regular(const Launch &l, hipStream_t stream) {
     const dim3 grid(l.grid), block(kThreads);
     if (l.kernel == kVectorKernel) {
         hipLaunchKernelGGL((vector_round_kernel<V, LDS>), grid, block, 0, stream, l.vec);
+        return;
+    }
+    if (l.kernel == kMeshShiftKernel) {
+        if constexpr (sizeof(V) == 16) {
+            if (l.stream_loads) {
+                hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, true>), grid, block, 0, stream, l.mesh_shift);
+                return;
+            }
+        }
+        hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, false>), grid, block, 0, stream, l.mesh_shift);
         return;
     }
     if constexpr (sizeof(V) == 16) {
@@ -337,14 +354,15 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             std::memset(&l, 0, sizeof(l));
             uint32_t k = 0;
             uint64_t total = 0;
-            if (uniform && !c.mesh) {
+            if (uniform && (!c.mesh || r.kind != ISO_ROUND_VECTOR)) {
                 // regular blocks: every entry has `chunks` units of the request's common width
+                // (on a mesh: shift rounds and same-rank copies; its s-exchange uses the block kernel)
                 const uint64_t chunks = size0 >> min_log2;
                 const uint64_t per_entry = p * chunks;
                 if (chunks > 0x7FFFFFFFu || per_entry > kMaxUnits) return ISO_ERR_TOO_LARGE;
                 k = (uint32_t)std::min<uint64_t>(kMaxUnits / per_entry, ents.size() - done);
                 total = per_entry * k;
-                l.kernel = r.kind == ISO_ROUND_VECTOR ? kVectorKernel : kShiftKernel;
+                l.kernel = r.kind == ISO_ROUND_VECTOR ? kVectorKernel : c.mesh ? kMeshShiftKernel : kShiftKernel;
                 const FastDiv dch = make_fastdiv((uint32_t)chunks), dk = make_fastdiv(k);
                 const FastDiv dp = make_fastdiv((uint32_t)p);
                 if (l.kernel == kVectorKernel) {
@@ -356,6 +374,22 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     for (int j = 0; j < c.d; ++j) {
                         l.vec.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
                         l.vec.inner[j] = (uint32_t)c.inner[j];
+                    }
+                } else if (l.kernel == kMeshShiftKernel) {
+                    const bool shift = r.kind == ISO_ROUND_SHIFT;
+                    MeshArgs &ma = l.mesh_shift;
+                    ma.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
+                    ma.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
+                    ma.shift_dim = shift ? r.dim : -1;
+                    ma.d = c.d;
+                    ma.d_chunks = dch;
+                    ma.d_k = dk;
+                    ma.d_p = dp;
+                    ma.entry_major = lay.slot_major;
+                    for (int j = 0; j < c.d; ++j) {
+                        if (c.periodic[(size_t)j]) ma.periodic_mask |= 1u << j;
+                        ma.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
+                        ma.inner_of[j] = (uint32_t)c.inner[j];
                     }
                 } else {
                     const bool shift = r.kind == ISO_ROUND_SHIFT;
@@ -419,7 +453,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             // streaming loads: all-to-all shift rounds of equal blocks (irregular blocks and the
             // s-exchange kernels are faster with cacheable loads)
             l.stream_loads = op == ISO_OP_ALLTOALL && r.kind != ISO_ROUND_VECTOR &&
-                             (l.kernel == kShiftKernel || (l.kernel == kBlockKernel && l.block.equal_units));
+                             (l.kernel == kShiftKernel || l.kernel == kMeshShiftKernel ||
+                              (l.kernel == kBlockKernel && l.block.equal_units));
             set_grid(l, (uint32_t)total, k);
             pending.push_back(pd);
             done += k;
@@ -445,6 +480,9 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
         if (pd.l.kernel == kVectorKernel) {
             pd.l.vec.entries = dev_entries + pd.first_entry;
             pd.l.vec.offsets = dev_offsets;
+        } else if (pd.l.kernel == kMeshShiftKernel) {
+            pd.l.mesh_shift.entries = dev_entries + pd.first_entry;
+            pd.l.mesh_shift.offsets = dev_offsets;
         } else if (pd.l.kernel == kBlockKernel) {
             pd.l.block.entries = dev_entries + pd.first_entry;
             pd.l.block.prefix = dev_prefix + pd.first_prefix;

@@ -267,8 +267,8 @@ struct BlockArgs {
 // Mesh: does the move of entry `en` happen at rank R (R - C^ref inside the mesh in every masked
 // dimension), and from which rank?  Offsets of non-periodic dimensions are signed values stored
 // as two's complement, so one unsigned comparison tests both ends of the dimension.
-template <int D>
-__device__ __forceinline__ bool mesh_source_rank_d(const BlockArgs &a, const DevEntry &en, uint32_t R,
+template <int D, typename Args>
+__device__ __forceinline__ bool mesh_source_rank_d(const Args &a, const DevEntry &en, uint32_t R,
                                                    uint32_t &srcR) {
     const uint32_t mask = (en.meta >> 8) & 0xFFFFu;
     const uint32_t *cref = a.offsets + (size_t)en.ref * a.d;
@@ -309,7 +309,8 @@ __device__ __forceinline__ bool mesh_source_rank_d(const BlockArgs &a, const Dev
     return true;
 }
 
-__device__ __forceinline__ bool mesh_source_rank(const BlockArgs &a, const DevEntry &en, uint32_t R,
+template <typename Args>
+__device__ __forceinline__ bool mesh_source_rank(const Args &a, const DevEntry &en, uint32_t R,
                                                  uint32_t &srcR) {
     switch (a.d) {
         case 1: return mesh_source_rank_d<1>(a, en, R, srcR);
@@ -402,6 +403,42 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
         case 1: move_unit<uint16_t, false>(dst, src, ch); break;
         default: move_unit<uint8_t, false>(dst, src, ch); break;
     }
+}
+
+// Shift rounds of equal blocks on a mesh: the shift kernel's decomposition (no prefix search, no
+// per-entry unit width) with the mesh's validity test.  Field names match what mesh_source_rank reads.
+struct MeshArgs {
+    const DevEntry *entries;
+    const uint32_t *offsets;   // [s][d] effective coordinates
+    TileMap map;
+    uint32_t total, k;
+    uint32_t inner, pj;        // rank stride and size of the moving dimension (1, 1 for a same-rank copy)
+    uint32_t entry_major;
+    int32_t shift_dim;         // -1: same-rank copy
+    int32_t d;
+    uint32_t periodic_mask;
+    static constexpr uint32_t vector_round = 0;
+    FastDiv d_chunks, d_k, d_p;
+    FastDiv d_dims[ISO_MAX_DIMS];
+    uint32_t inner_of[ISO_MAX_DIMS];
+};
+
+template <typename V, bool LDS, bool NTL>
+__global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshArgs a) {
+    __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
+    const EntryTable<LDS> table(a.entries, a.k, lds);
+    uint32_t tile;
+    if (!tile_of_block(a.map, tile)) return;
+    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
+    if (u >= a.total) return;
+    uint32_t t, ch, R, e;
+    fast_divmod(u, a.d_chunks, t, ch);
+    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
+    else fast_divmod(t, a.d_k, R, e);
+    const DevEntry en = table[e];
+    uint32_t srcR = R;
+    if (!mesh_source_rank(a, en, R, srcR)) return;        // no source: leave the destination as it is
+    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
 }
 
 // Plain streaming copy with the same access shape: the measured ceiling.
