@@ -57,3 +57,15 @@ def test_config_table_matches_the_named_workloads():
     assert all(-3 <= x <= 3 for v in c5.offsets for x in v)
     assert gen.random_distinct(5, -3, 3, 40, 1606_07676) == list(c5.offsets)
     assert gen.get_config("2") is c[1] and gen.get_config(c[2].name) is c[2]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark runs on one GPU only and must say so instead of starting ranks."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                         stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
+    assert out.returncode != 0 and out.stdout == ""
+    assert "ONE GPU" in out.stderr
