@@ -28,6 +28,7 @@ CASES = [
     ((37, 11), gen.moore(2, 2)),                          # several tiles, ragged tail
     ((2, 2, 2, 2, 2), gen.moore(5, 1)),                   # 162 entries in one round: table too big for LDS
     ((8, 4, 8), gen.moore(3, 3)),                         # s = 342
+    ((7, 5, 6), gen.positive_octant(3, 3)),               # s = 63, asymmetric
 ]
 BLOCK_SIZES = [16, 48, 256, 1, 6, 1040]
 
@@ -71,6 +72,23 @@ def test_slot_major_every_byte(case, alg):
         wantg = orc.allgather(dims, offsets, one_h).transpose(1, 0, 2)
         recv, _ = _run(comm, iso.ISO_OP_ALLGATHER, alg, m, torch.from_numpy(one_h).to(DEV), p, s)
         assert np.array_equal(recv.cpu().numpy(), wantg), f"ag dims={dims} m={m} alg={alg}"
+
+
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_ONEHOP],
+                         ids=lambda a: ALG_NAMES[a])
+def test_slot_major_shales_neighbourhood(alg):
+    """Section 6's 1396-neighbour shells on a 9 x 8 x 8 torus: 1396 planes, launches with several
+    hundred entries."""
+    dims, offsets, m = (9, 8, 8), gen.shales(3, (3, 7)), 16
+    p, s = 576, len(offsets)
+    comm = _comm(dims, offsets)
+    send_h = gen.alltoall_send(31, p, s, m)
+    send = torch.from_numpy(np.ascontiguousarray(send_h.transpose(1, 0, 2))).to(DEV)
+    recv, _ = _run(comm, iso.ISO_OP_ALLTOALL, alg, m, send, p, s)
+    assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h).transpose(1, 0, 2))
+    one_h = gen.allgather_send(32, p, m)
+    recv, _ = _run(comm, iso.ISO_OP_ALLGATHER, alg, m, torch.from_numpy(one_h).to(DEV), p, s)
+    assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, one_h).transpose(1, 0, 2))
 
 
 def test_slot_major_on_a_mesh_and_layout_argument():

@@ -35,6 +35,7 @@ SMALL = [
     ((1, 1), [(0, 0), (3, -2)]),                          # a single process
     ((2, 2, 2, 2, 2), gen.moore(5, 1)),                   # 162 entries in one round: table too big for LDS
     ((8, 4, 8), gen.moore(3, 3)),                         # s = 342, radius > 1, wrap-around aliases
+    ((7, 5, 6), gen.positive_octant(3, 3)),               # s = 63, the asymmetric neighbourhood of Section 4
 ]
 BLOCK_SIZES = [16, 48, 256, 1, 6, 20, 8, 1040]
 
@@ -87,6 +88,38 @@ def test_small_allgather_every_byte(case, alg):
         recv, _ = _run(dims, offsets, iso.ISO_OP_ALLGATHER, alg, m, send)
         want = orc.allgather(dims, offsets, send_h)
         assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} m={m} alg={alg}"
+
+
+@pytest.mark.parametrize("alg", ALGS, ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("dims", [(15, 16, 17), (9, 8, 8)], ids=["no_alias", "aliased"])
+def test_shales_neighbourhood(dims, alg):
+    """Section 6's largest neighbourhood: the Chebyshev shells of radius 3 and 7 in three
+    dimensions, 1396 neighbours.  Every coordinate value from -7 to 7 occurs, so the
+    torus-direct schedule has one round per dimension and non-zero residue (Section 5):
+    14 * 3 = 42 on a torus whose sizes exceed 14; on the 9 x 8 x 8 torus (576 processes as
+    in the paper's runs) values alias and 8 + 7 + 7 = 22 residues are left.  Rounds hold up
+    to several hundred entries (more than the LDS table takes)."""
+    offsets = gen.shales(3, (3, 7))
+    p, s = int(np.prod(dims)), len(offsets)
+    assert s == 1396
+    direct_rounds = sum(len({c[j] % dims[j] for c in offsets} - {0}) for j in range(3))
+    # one-hop schedule (Section 3.1): per dimension the longest walk up plus the longest walk down,
+    # counted on the coordinates as given
+    onehop_rounds = sum(max(c[j] for c in offsets) - min(c[j] for c in offsets) for j in range(3))
+    for m in (16, 40):
+        send_h = gen.alltoall_send(77, p, s, m)
+        send = torch.from_numpy(send_h).to(DEV)
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, alg, m, send)
+        assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h)), f"alltoall m={m}"
+        assert info["launches"] == {iso.ISO_ALG_COMBINED: direct_rounds, iso.ISO_ALG_COMBINED_BYDIM: 3,
+                                    iso.ISO_ALG_SX_ROUNDS: s, iso.ISO_ALG_SX_FUSED: 1,
+                                    iso.ISO_ALG_ONEHOP: onehop_rounds}[alg]
+        del send, recv
+        send_h = gen.allgather_send(78, p, m)
+        send = torch.from_numpy(send_h).to(DEV)
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLGATHER, alg, m, send)
+        assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, send_h)), f"allgather m={m}"
+    assert direct_rounds == (42 if dims[0] == 15 else 22) and onehop_rounds == 42
 
 
 @pytest.mark.parametrize("misalign,vec", [(0, 16), (8, 8), (4, 4), (2, 2), (1, 1)])
