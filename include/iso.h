@@ -143,7 +143,9 @@ typedef struct {
 typedef struct {
     int32_t op, algorithm;
     int32_t launches;
-    int32_t vector_bytes;        /* width of the loads/stores chosen from alignment: 16..1 */
+    int32_t vector_bytes;        /* width of the loads/stores: the largest power of two that is
+                                  * at most 16 and at most the smallest non-empty block; buffer
+                                  * addresses need no alignment                               */
     int64_t p, s;
     uint64_t block_bytes;        /* m                                                       */
     int64_t entries;             /* block-moves per rank                                    */
@@ -201,9 +203,9 @@ int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t
  * recvbuf:   device, [p][s][m]; after completion block (R,i) holds what rank
  *            R (-) C^i sent (all-to-all: its i-th block; allgather: its block).
  * m:         block size in bytes, any value >= 0 (m == 0 or s == 0: no-op).
- *            Loads and stores are 16 bytes wide when m and the three base
- *            addresses are multiples of 16, else the widest power of two that
- *            divides them all.
+ *            Loads and stores are 16 bytes wide for m >= 16 (below: the largest
+ *            power of two that is at most m); the buffers need no alignment.
+ *            Blocks whose ends fall on 32-byte boundaries are written fastest.
  * workspace: device, at least iso_workspace_bytes() bytes (NULL allowed when
  *            that is 0).  Contents are scratch while a collective runs.
  * The three ranges must not overlap (ISO_ERR_OVERLAP); in-place operation is

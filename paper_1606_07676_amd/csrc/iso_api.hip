@@ -578,7 +578,7 @@ int iso_copy_reference(const void *src, void *dst, size_t bytes, void *hip_strea
     if ((st = iso::check_device_range(src, bytes)) != ISO_SUCCESS) return st;
     if ((st = iso::check_device_range(dst, bytes)) != ISO_SUCCESS) return st;
     hipStream_t stream = (hipStream_t)hip_stream;
-    const uint32_t l2 = iso::unit_log2_of({(uint64_t)bytes, (uint64_t)(uintptr_t)src, (uint64_t)(uintptr_t)dst});
+    const uint32_t l2 = iso::common_alignment_log2({(uint64_t)bytes, (uint64_t)(uintptr_t)src, (uint64_t)(uintptr_t)dst});
     const uint64_t units = bytes >> l2;
     const uint64_t blocks = (units + iso::kThreads - 1) / iso::kThreads;
     if (blocks > 0x7FFFFFFFull) return ISO_ERR_TOO_LARGE;

@@ -39,6 +39,7 @@ struct Launch {
     bool lds_table;
     bool mesh;
     bool stream_loads;     // every source block is read exactly once in this launch: non-temporal loads
+    bool tail;             // regular kernels: the last unit of a block overlaps the one before it
 
     ShiftArgs shift;
     VectorArgs vec;
@@ -84,12 +85,22 @@ inline int check_device_range(const void *ptr, size_t len) {
     return ISO_SUCCESS;
 }
 
-// log2 of the widest power-of-two unit (<= 16 bytes) that divides all the values
-inline uint32_t unit_log2_of(std::initializer_list<uint64_t> values) {
+// log2 of the widest power of two (<= 16) that divides all the values: the access width of the
+// plain reference copy, which keeps naturally aligned accesses
+inline uint32_t common_alignment_log2(std::initializer_list<uint64_t> values) {
     uint64_t bits = 0;
     for (uint64_t v : values) bits |= v;
     uint32_t l = 4;
     while (l > 0 && (bits & ((uint64_t(1) << l) - 1))) --l;
+    return l;
+}
+
+// log2 of the unit width for a block of `size` >= 1 bytes: the largest power of two that is
+// at most 16 and at most the size (the last unit of a block overlaps its predecessor when the
+// width does not divide the size; addresses need no alignment)
+inline uint32_t unit_log2_of(uint64_t size) {
+    uint32_t l = 4;
+    while (l > 0 && (uint64_t(1) << l) > size) --l;
     return l;
 }
 
@@ -155,36 +166,43 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k) {
 
 // Streaming loads exist for the shift kernel at the 16-byte width only (narrower
 // units are the slow path anyway).
-template <typename V, bool LDS>
+template <typename V, bool LDS, bool TAIL>
 void enqueue_regular(const Launch &l, hipStream_t stream) {
     const dim3 grid(l.grid), block(kThreads);
     if (l.kernel == kVectorKernel) {
-        hipLaunchKernelGGL((vector_round_kernel<V, LDS>), grid, block, 0, stream, l.vec);
+        hipLaunchKernelGGL((vector_round_kernel<V, LDS, TAIL>), grid, block, 0, stream, l.vec);
         return;
     }
     if (l.kernel == kMeshShiftKernel) {
         if constexpr (sizeof(V) == 16) {
             if (l.stream_loads) {
-                hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, true>), grid, block, 0, stream, l.mesh_shift);
+                hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, true, TAIL>), grid, block, 0, stream, l.mesh_shift);
                 return;
             }
         }
-        hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, false>), grid, block, 0, stream, l.mesh_shift);
+        hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, false, TAIL>), grid, block, 0, stream, l.mesh_shift);
         return;
     }
     if constexpr (sizeof(V) == 16) {
         if (l.stream_loads) {
-            hipLaunchKernelGGL((shift_round_kernel<V, LDS, true>), grid, block, 0, stream, l.shift);
+            hipLaunchKernelGGL((shift_round_kernel<V, LDS, true, TAIL>), grid, block, 0, stream, l.shift);
             return;
         }
     }
-    hipLaunchKernelGGL((shift_round_kernel<V, LDS, false>), grid, block, 0, stream, l.shift);
+    hipLaunchKernelGGL((shift_round_kernel<V, LDS, false, TAIL>), grid, block, 0, stream, l.shift);
 }
 
 template <typename V>
 void enqueue_width(const Launch &l, hipStream_t stream) {
-    if (l.lds_table) enqueue_regular<V, true>(l, stream);
-    else enqueue_regular<V, false>(l, stream);
+    if constexpr (sizeof(V) > 1) {
+        if (l.tail) {                     // the unit width does not divide the block size
+            if (l.lds_table) enqueue_regular<V, true, true>(l, stream);
+            else enqueue_regular<V, false, true>(l, stream);
+            return;
+        }
+    }
+    if (l.lds_table) enqueue_regular<V, true, false>(l, stream);
+    else enqueue_regular<V, false, false>(l, stream);
 }
 
 template <bool LDS, bool MESH>
@@ -311,15 +329,20 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             HostEntry he{};
             he.size = entry_size(pe);
             if (he.size == 0) continue;                       // empty blocks make no move
-            place(pe.src_buf, pe.src_slot, he.de.src, he.de.src_stride);
-            place(pe.dst_buf, pe.dst_slot, he.de.dst, he.de.dst_stride);
+            uint64_t src_stride = 0, dst_stride = 0;
+            place(pe.src_buf, pe.src_slot, he.de.src, src_stride);
+            place(pe.dst_buf, pe.dst_slot, he.de.dst, dst_stride);
             // the kernels multiply a rank by a 32-bit stride
-            if ((he.de.src_stride | he.de.dst_stride) >> 32) return ISO_ERR_TOO_LARGE;
+            if ((src_stride | dst_stride) >> 32) return ISO_ERR_TOO_LARGE;
+            he.de.src_stride = (uint32_t)src_stride;
+            he.de.dst_stride = (uint32_t)dst_stride;
             he.de.shift = r.kind == ISO_ROUND_VECTOR ? (uint32_t)pe.neighbor : (uint32_t)pe.shift;
-            const uint32_t l2 = unit_log2_of({he.size, he.de.src, he.de.dst, he.de.src_stride, he.de.dst_stride});
-            const uint64_t units = he.size >> l2;
+            const uint32_t l2 = unit_log2_of(he.size);
+            const uint64_t width = uint64_t(1) << l2;
+            const uint64_t units = (he.size + width - 1) >> l2;
             if (units > 0x7FFFFFFFu) return ISO_ERR_TOO_LARGE;
             he.de.units = (uint32_t)units;
+            he.de.last_offset = he.size - width;
             he.de.ref = (uint32_t)pe.ref;
             // mesh: the non-periodic dimensions routed so far in which C^ref is non-zero
             uint32_t mask = 0;
@@ -357,7 +380,9 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             if (uniform && (!c.mesh || r.kind != ISO_ROUND_VECTOR)) {
                 // regular blocks: every entry has `chunks` units of the request's common width
                 // (on a mesh: shift rounds and same-rank copies; its s-exchange uses the block kernel)
-                const uint64_t chunks = size0 >> min_log2;
+                const uint64_t width = uint64_t(1) << min_log2;
+                const uint64_t chunks = (size0 + width - 1) >> min_log2;
+                l.tail = (size0 & (width - 1)) != 0;
                 const uint64_t per_entry = p * chunks;
                 if (chunks > 0x7FFFFFFFu || per_entry > kMaxUnits) return ISO_ERR_TOO_LARGE;
                 k = (uint32_t)std::min<uint64_t>(kMaxUnits / per_entry, ents.size() - done);
@@ -371,6 +396,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.vec.d_k = dk;
                     l.vec.d_p = dp;
                     l.vec.entry_major = lay.slot_major;
+                    l.vec.last_offset = size0 - width;
                     for (int j = 0; j < c.d; ++j) {
                         l.vec.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
                         l.vec.inner[j] = (uint32_t)c.inner[j];
@@ -386,6 +412,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     ma.d_k = dk;
                     ma.d_p = dp;
                     ma.entry_major = lay.slot_major;
+                    ma.last_offset = size0 - width;
                     for (int j = 0; j < c.d; ++j) {
                         if (c.periodic[(size_t)j]) ma.periodic_mask |= 1u << j;
                         ma.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
@@ -399,6 +426,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.shift.d_k = dk;
                     l.shift.d_p = dp;
                     l.shift.entry_major = lay.slot_major;
+                    l.shift.last_offset = size0 - width;
                     l.shift.d_inner = make_fastdiv(l.shift.inner);
                     l.shift.d_pj = make_fastdiv(l.shift.pj);
                 }

@@ -46,14 +46,15 @@ constexpr uint32_t kLdsEntries = 128;   // rounds with at most this many entries
 struct alignas(16) DevEntry {
     uint64_t src;          // address of rank 0's source block
     uint64_t dst;          // address of rank 0's destination block
-    uint64_t src_stride;   // bytes between consecutive ranks in the source buffer; below 2^32 (checked
-    uint64_t dst_stride;   // when the request is bound), so that rank * stride + base is one 32x32+64 multiply-add
+    uint32_t src_stride;   // bytes between consecutive ranks in the source buffer; below 2^32 (checked
+    uint32_t dst_stride;   // when the request is bound), so that rank * stride + base is one 32x32+64 multiply-add
     uint32_t shift;        // SHIFT rounds: residue v; VECTOR rounds: neighbour index
-    uint32_t units;        // block launches: block size / unit width of this entry
+    uint32_t units;        // block launches: units of this entry's block, block size / unit width rounded up
     uint32_t meta;         // block launches: bits 0-7 log2 of the unit width in bytes;
                            // bits 8-23 (mesh) dimensions in which R - C^ref must be inside the mesh;
                            // bits 24-29 the two shifts of the division by `units` (entry-major order)
     uint32_t ref;          // mesh: neighbour whose coordinates decide whether the move happens
+    uint64_t last_offset;  // block launches: block size - unit width, the byte offset of the last unit
 };
 
 // Workgroup -> tile mapping.  The hardware hands consecutive workgroup ids to
@@ -82,6 +83,7 @@ struct ShiftArgs {
     uint32_t pj;           // its size
     uint32_t entry_major;  // unit order (entry, rank, chunk) instead of (rank, entry, chunk)
     FastDiv d_chunks, d_k, d_inner, d_pj, d_p;
+    uint64_t last_offset;  // block size - unit width (read by the TAIL instantiations only)
 };
 
 struct VectorArgs {
@@ -95,28 +97,55 @@ struct VectorArgs {
     FastDiv d_chunks, d_k, d_p;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner[ISO_MAX_DIMS];
+    uint64_t last_offset;
 };
 
 typedef uint32_t vec16_t __attribute__((ext_vector_type(4)));
 typedef uint32_t vec8_t __attribute__((ext_vector_type(2)));
 
-// One unit from byte address `src` to byte address `dst`, both in global memory
-// (the address space is spelled out so that the accesses are global_load /
-// global_store, not flat ones).  NTL: streaming load.
+// A block of `size` bytes is moved in units of w bytes, w the largest power of two that is at
+// most 16 and at most `size`: ceil(size / w) units, unit c at byte offset min(c * w, size - w).
+// When w does not divide the size the last unit overlaps the one before it; both carry the same
+// bytes of the same block, so the doubly written bytes get the same value twice.  Addresses
+// need no alignment: the unit types are declared with alignment 1 and global memory accesses of
+// any width take any address on this target.
+template <typename V>
+struct Unaligned {
+    typedef V type __attribute__((aligned(1)));
+};
+
+// The unit at byte offset `off` of the block at byte address `src` to the same offset of the
+// block at `dst`, both in global memory (the address space is spelled out so that the accesses
+// are global_load / global_store, not flat ones).  NTL: streaming load.
 template <typename V, bool NTL>
-__device__ __forceinline__ void move_unit(uint64_t dst, uint64_t src, uint32_t ch) {
-    typedef const V __attribute__((address_space(1))) *src_ptr;
-    typedef V __attribute__((address_space(1))) *dst_ptr;
-    const src_ptr sp = (src_ptr)src + ch;
+__device__ __forceinline__ void move_unit(uint64_t dst, uint64_t src, uint64_t off) {
+    typedef typename Unaligned<V>::type UV;
+    typedef const UV __attribute__((address_space(1))) *src_ptr;
+    typedef UV __attribute__((address_space(1))) *dst_ptr;
+    const src_ptr sp = (src_ptr)(src + off);
     V v;
     if constexpr (NTL) v = __builtin_nontemporal_load(sp);
     else v = *sp;
-    __builtin_nontemporal_store(v, (dst_ptr)dst + ch);
+    __builtin_nontemporal_store(v, (dst_ptr)(dst + off));
+}
+
+template <typename V>
+__device__ __forceinline__ uint64_t unit_offset(uint32_t ch, uint64_t last_offset) {
+    const uint64_t off = (uint64_t)ch * sizeof(V);
+    return off < last_offset ? off : last_offset;
+}
+
+// TAIL: the width does not divide the block size.  The regular kernels are instantiated
+// without it as well: the comparison and selects cost 2 % on the round kernel.
+template <typename V, bool TAIL>
+__device__ __forceinline__ uint64_t unit_offset_if(uint32_t ch, uint64_t last_offset) {
+    if constexpr (TAIL) return unit_offset<V>(ch, last_offset);
+    else return (uint64_t)ch * sizeof(V);
 }
 
 // Address of rank R's block: base + R * stride with the stride known to fit 32 bits.
-__device__ __forceinline__ uint64_t block_address(uint64_t base, uint32_t R, uint64_t stride) {
-    return base + (uint64_t)R * (uint32_t)stride;
+__device__ __forceinline__ uint64_t block_address(uint64_t base, uint32_t R, uint32_t stride) {
+    return base + (uint64_t)R * stride;
 }
 
 // Entry table of the launch: from LDS (staged once per workgroup) when it fits,
@@ -189,7 +218,7 @@ __device__ __forceinline__ uint32_t vector_source_rank(uint32_t R, const uint32_
     return srcR;
 }
 
-template <typename V, bool LDS, bool NTL>
+template <typename V, bool LDS, bool NTL, bool TAIL>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
@@ -209,10 +238,11 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     // the true result lies in [0, p))
     uint32_t srcR = R - en.shift * a.inner;
     if (rj < en.shift) srcR += a.pj * a.inner;
-    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
+    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride),
+                      unit_offset_if<V, TAIL>(ch, a.last_offset));
 }
 
-template <typename V, bool LDS>
+template <typename V, bool LDS, bool TAIL>
 __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
@@ -226,12 +256,13 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
     else fast_divmod(t, a.d_k, R, e);
     const DevEntry en = table[e];
     const uint32_t srcR = vector_source_rank(R, a.offsets + (size_t)en.shift * a.d, a.d, a.d_dims, a.inner);
-    move_unit<V, false>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
+    move_unit<V, false>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride),
+                        unit_offset_if<V, TAIL>(ch, a.last_offset));
 }
 
 // Irregular blocks (the v/w interfaces of Section 2): every entry has its own
-// block size and its own unit width (16 bytes where size and alignment allow,
-// narrower otherwise, e.g. a 1-byte corner block next to a 16 KiB face block).
+// block size and its own unit width (16 bytes for blocks of at least 16 bytes,
+// narrower below, e.g. a 1-byte corner block next to a 16 KiB face block).
 // A rank's units are the concatenation of its entries' units; `prefix[e]` is
 // the first unit of entry e.  The flat index is split into (rank, unit in row),
 // the entry is found by binary search in the prefix array.  On slot-major
@@ -397,10 +428,10 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     const uint64_t src = block_address(en.src, srcR, en.src_stride);
     const uint64_t dst = block_address(en.dst, R, en.dst_stride);
     switch (en.meta & 0xFFu) {
-        case 4: move_unit<vec16_t, NTL>(dst, src, ch); break;
-        case 3: move_unit<vec8_t, false>(dst, src, ch); break;
-        case 2: move_unit<uint32_t, false>(dst, src, ch); break;
-        case 1: move_unit<uint16_t, false>(dst, src, ch); break;
+        case 4: move_unit<vec16_t, NTL>(dst, src, unit_offset<vec16_t>(ch, en.last_offset)); break;
+        case 3: move_unit<vec8_t, false>(dst, src, unit_offset<vec8_t>(ch, en.last_offset)); break;
+        case 2: move_unit<uint32_t, false>(dst, src, unit_offset<uint32_t>(ch, en.last_offset)); break;
+        case 1: move_unit<uint16_t, false>(dst, src, unit_offset<uint16_t>(ch, en.last_offset)); break;
         default: move_unit<uint8_t, false>(dst, src, ch); break;
     }
 }
@@ -421,9 +452,10 @@ struct MeshArgs {
     FastDiv d_chunks, d_k, d_p;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
+    uint64_t last_offset;
 };
 
-template <typename V, bool LDS, bool NTL>
+template <typename V, bool LDS, bool NTL, bool TAIL>
 __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
@@ -438,7 +470,8 @@ __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshAr
     const DevEntry en = table[e];
     uint32_t srcR = R;
     if (!mesh_source_rank(a, en, R, srcR)) return;        // no source: leave the destination as it is
-    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride), ch);
+    move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride),
+                      unit_offset_if<V, TAIL>(ch, a.last_offset));
 }
 
 // Plain streaming copy with the same access shape: the measured ceiling.

@@ -122,15 +122,53 @@ def test_shales_neighbourhood(dims, alg):
     assert direct_rounds == (42 if dims[0] == 15 else 22) and onehop_rounds == 42
 
 
-@pytest.mark.parametrize("misalign,vec", [(0, 16), (8, 8), (4, 4), (2, 2), (1, 1)])
-def test_vector_width_follows_alignment(misalign, vec):
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_SX_FUSED], ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("send_off,recv_off", [(0, 0), (8, 8), (8, 0), (4, 12), (2, 2), (1, 1), (1, 2), (3, 0),
+                                               (0, 13)])
+def test_unaligned_buffers_keep_the_full_unit_width(send_off, recv_off, alg):
+    """Buffer addresses need no alignment: blocks of 16 bytes and more move in 16-byte units
+    wherever the buffers start, and the bytes around the buffers stay as they were."""
     dims, offsets = (6, 5), gen.moore(2, 1)
-    p, s, m = 30, 8, 64
-    send_h = gen.alltoall_send(5, p, s, m)
+    p, s = 30, 8
+    for m in (64, 52, 17):
+        n = p * s * m
+        send_h = gen.alltoall_send(5, p, s, m)
+        send_store = torch.full((n + 48,), 0xAB, dtype=torch.uint8, device=DEV)
+        send = send_store[16 + send_off:16 + send_off + n]
+        send.copy_(torch.from_numpy(send_h.reshape(-1)).to(DEV))
+        recv_store = torch.full((n + 48,), 0xEE, dtype=torch.uint8, device=DEV)
+        recv = recv_store[16 + recv_off:16 + recv_off + n]
+        comm = _comm(dims, offsets)
+        wsb = iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, m)
+        work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoall_init(send, recv, m, work, comm, alg)
+        assert iso.iso_request_info(req)["vector_bytes"] == 16
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        iso.iso_request_free(req)
+        assert np.array_equal(recv.cpu().numpy().reshape(p, s, m), orc.alltoall(dims, offsets, send_h)), (m, alg)
+        out = recv_store.cpu().numpy()
+        assert (out[:16 + recv_off] == 0xEE).all() and (out[16 + recv_off + n:] == 0xEE).all()
+        assert np.array_equal(send.cpu().numpy(), send_h.reshape(-1))
+
+
+@pytest.mark.parametrize("m,vec", [(1, 1), (2, 2), (3, 2), (4, 4), (5, 4), (7, 4), (8, 8), (9, 8), (15, 8),
+                                   (16, 16), (17, 16), (31, 16), (33, 16), (100, 16), (1039, 16)])
+def test_unit_width_follows_the_block_size(m, vec):
+    """The unit is the largest power of two up to 16 bytes that fits the block; a block whose
+    size is not a multiple of it ends with a unit that overlaps the one before."""
+    dims, offsets = (37, 11), gen.moore(2, 2)
+    p, s = 407, 24
+    send_h = gen.alltoall_send(6, p, s, m)
     send = torch.from_numpy(send_h).to(DEV)
-    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m, send, misalign=misalign)
-    assert info["vector_bytes"] == vec
-    assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h))
+    for alg in ALGS:
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, alg, m, send)
+        assert info["vector_bytes"] == vec
+        assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h)), (m, alg)
+    one_h = gen.allgather_send(7, p, m)
+    for alg in ALGS:
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLGATHER, alg, m, torch.from_numpy(one_h).to(DEV))
+        assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, one_h)), (m, alg)
 
 
 def test_restart_and_side_stream_give_the_same_result():
@@ -315,23 +353,28 @@ def test_named_workloads_full_size(key, alg):
 
 
 def test_round_is_split_when_the_unit_index_would_overflow():
-    """Byte-wide units (receive buffer misaligned by one byte) and 16 KiB blocks on the
-    32^3 torus: one round of 9 entries has 9 * 2^29 units, more than a launch's 32-bit
-    unit index holds, so the binding must split rounds over several launches."""
-    dims, offsets, m, seed = (32, 32, 32), gen.moore(3, 1), 16384, 31
-    p, s = 32768, 26
-    send = gen.alltoall_send_torch(seed, p, s, m, device=DEV)
-    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m, send, misalign=1)
-    assert info["vector_bytes"] == 1
-    assert info["launches"] == 12               # 6 rounds, each 7 + 2 entries
+    """Two blocks of 8 MiB + 8 bytes per rank on 4096 ranks, both moved in the single round of
+    this neighbourhood: 2 * 4096 * 524289 units of 16 bytes, more than a launch's 32-bit unit
+    index holds, so the binding must split the round over two launches.  64 GiB per buffer;
+    the last unit of every block overlaps the one before it."""
+    dims, offsets, m, seed = (64, 64), [(1, 0), (1, 0)], (8 << 20) + 8, 31
+    p, s = 4096, 2
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < 2 * p * s * m + (8 << 30):
+        pytest.skip("needs 136 GiB of free device memory")
+    send = gen.alltoall_send_torch(seed, p, s, m, device=DEV, rank_chunk=4)
+    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m, send)
+    assert info["vector_bytes"] == 16
+    assert info["launches"] == 2                # 1 round, one entry per launch
     src = orc.source_ranks(dims, offsets)
     slots = torch.arange(s, device=DEV)[None, :]
-    chunk = (256 << 20) // (s * m)
+    chunk = 8
     for lo in range(0, p, chunk):
         hi = min(p, lo + chunk)
         want = gen.block_bytes_torch(seed, torch.from_numpy(src[lo:hi]).to(DEV), slots, m)
         assert torch.equal(recv[lo:hi], want), f"ranks {lo}:{hi}"
-    del send, recv
+    del send, recv, want
     torch.cuda.empty_cache()
 
 
