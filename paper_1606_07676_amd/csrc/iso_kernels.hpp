@@ -233,7 +233,6 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     const uint32_t q = fast_div(R, a.d_inner);
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
     const DevEntry en = table[e];
-    // v steps back along the dimension, with wrap-around
     // v steps back along the dimension, around the ring where that passes coordinate 0 (modulo 2^32;
     // the true result lies in [0, p))
     uint32_t srcR = R - en.shift * a.inner;
