@@ -29,7 +29,7 @@ def _case(rng, mesh):
     if rng.integers(0, 3) == 0:
         offsets.append((0,) * d)
     periodic = tuple(int(x) for x in rng.integers(0, 2, size=d)) if mesh else (1,) * d
-    m = int(rng.choice([1, 3, 4, 8, 16, 24, 32, 48, 100, 256, 272, 1024]))
+    m = int(rng.choice([1, 3, 4, 5, 8, 16, 17, 24, 31, 32, 48, 100, 250, 256, 272, 1024]))
     return dims, periodic, offsets, m
 
 
@@ -78,3 +78,86 @@ def test_random_mesh_every_byte(seed):
         assert np.array_equal(got, want_a2a), (dims, periodic, offsets, m, alg)
         got = _run(comm, iso.ISO_OP_ALLGATHER, alg, m, ag, p, s)
         assert np.array_equal(got, want_ag), (dims, periodic, offsets, m, alg)
+
+
+def _random_sizes(rng, s):
+    """per-neighbour block sizes: empty, tiny, around the unit width, large"""
+    pool = [0, 1, 2, 3, 7, 8, 15, 16, 17, 31, 33, 64, 100, 255, 256, 300]
+    return [int(rng.choice(pool)) for _ in range(s)]
+
+
+def _gapped_displacements(rng, sizes, order):
+    """blocks laid out in `order` with random gaps of 0..4 bytes; returns (displs, extent)"""
+    displs, at = [0] * len(sizes), int(rng.integers(0, 4))
+    for i in order:
+        displs[i] = at
+        at += sizes[i] + int(rng.integers(0, 5))
+    return displs, at + int(rng.integers(0, 4))
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_irregular_every_byte(seed):
+    """All-to-allv and allgatherv on random tori (even seeds) and meshes (odd seeds) with random
+    per-neighbour sizes and gapped, byte-aligned displacements, rank-major rows and slot-major
+    planes; bytes between blocks must stay untouched."""
+    rng = np.random.default_rng(7000 + seed)
+    mesh = seed % 2 == 1
+    dims, periodic, offsets, _ = _case(rng, mesh)
+    d, p, s = len(dims), int(np.prod(dims)), len(offsets)
+    arr = np.asarray(offsets, np.int32).reshape(s, d)
+    comm = iso.iso_neighborhood_create_mesh(dims, periodic, arr) if mesh else iso.iso_neighborhood_create(dims, arr)
+    if mesh:
+        src, valid = orc.source_ranks_mesh(dims, periodic, offsets)
+    else:
+        src, valid = orc.source_ranks(dims, offsets), np.ones((p, s), bool)
+    sizes = _random_sizes(rng, s)
+    sd, sext = _gapped_displacements(rng, sizes, range(s))
+    rd, rext = _gapped_displacements(rng, sizes, reversed(range(s)))
+    send_h = rng.integers(0, 256, size=(p, sext), dtype=np.uint8)
+    want = np.full((p, rext), 0xEE, np.uint8)
+    for i in range(s):
+        v = valid[:, i]
+        want[v, rd[i]:rd[i] + sizes[i]] = send_h[src[v, i], sd[i]:sd[i] + sizes[i]]
+    # slot-major: plane i holds block i of all ranks, p * size_i bytes, planes with gaps
+    pd, pext = _gapped_displacements(rng, [p * z for z in sizes], range(s))
+    psend_h = rng.integers(0, 256, size=pext, dtype=np.uint8)
+    pwant = np.full(pext, 0xEE, np.uint8)
+    for i in range(s):
+        plane = psend_h[pd[i]:pd[i] + p * sizes[i]].reshape(p, sizes[i])
+        out = pwant[pd[i]:pd[i] + p * sizes[i]].reshape(p, sizes[i])
+        v = valid[:, i]
+        out[v] = plane[src[v, i]]
+    # allgatherv: one block of g bytes per rank
+    g = int(rng.choice([1, 5, 16, 40, 257]))
+    one_h = rng.integers(0, 256, size=(p, g + 3), dtype=np.uint8)
+    gd, gext = _gapped_displacements(rng, [g] * s, range(s))
+    gwant = np.full((p, gext), 0xEE, np.uint8)
+    for i in range(s):
+        v = valid[:, i]
+        gwant[v, gd[i]:gd[i] + g] = one_h[src[v, i], :g]
+    send, psend, one = (torch.from_numpy(x).to(DEV) for x in (send_h, psend_h, one_h))
+    for alg in (MESH_ALGS if mesh else TORUS_ALGS):
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+        work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+        recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        iso.iso_request_free(req)
+        assert np.array_equal(recv.cpu().numpy(), want), ("rows", dims, periodic, offsets, sizes, alg)
+        precv = torch.full((pext,), 0xEE, dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoallv_init_layout(psend, sizes, pd, 0, precv, sizes, pd, 0,
+                                                     iso.ISO_LAYOUT_SLOT_MAJOR, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        iso.iso_request_free(req)
+        assert np.array_equal(precv.cpu().numpy(), pwant), ("planes", dims, periodic, offsets, sizes, alg)
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, alg, [g] * s)
+        work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+        grecv = torch.full((p, gext), 0xEE, dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_allgatherv_init(one, g, g + 3, grecv, [g] * s, gd, gext, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        iso.iso_request_free(req)
+        assert np.array_equal(grecv.cpu().numpy(), gwant), ("allgatherv", dims, periodic, offsets, g, alg)
+    assert np.array_equal(send.cpu().numpy(), send_h) and np.array_equal(psend.cpu().numpy(), psend_h)
