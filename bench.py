@@ -315,27 +315,6 @@ def main():
             extras[f"combined_{op_name[op]}_only"] = {
                 "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
                 "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
-        if len(reqs) == 2:
-            # the two collectives are independent (different buffers): started on two streams of the
-            # default priority, their launches overlap each other's ramp-up and tail
-            side = torch.cuda.Stream()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            joined = torch.cuda.Event()
-            for timed in (False, True):
-                torch.cuda.synchronize()
-                e0.record(stream)
-                side.wait_event(e0)
-                for _ in range(ksteps):
-                    iso.iso_start(reqs[0], stream)
-                    iso.iso_start(reqs[1], side)
-                joined.record(side)
-                stream.wait_event(joined)
-                e1.record(stream)
-                torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / ksteps
-            extras["combined_two_streams"] = {"ms_per_step": round(ms, 5),
-                                              "delivered_GBs": round(delivered / ms / 1e6, 1),
-                                              "moved_GBs": round(moved / ms / 1e6, 1), "launches": launches}
         for r in reqs:                                  # the same requests replayed as HIP graphs
             iso.iso_request_set_graph(r, True)
         ms = time_steps(reqs, ksteps, 3) / ksteps
