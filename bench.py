@@ -408,6 +408,27 @@ def main():
                 iso.iso_request_free(r)
             del rs, keepalive
             torch.cuda.empty_cache()
+        # the all-to-all with every rank's row padded by 128 bytes (the irregular interface's extents):
+        # where the row size s*m is a multiple of 4 KiB, all blocks of a round sit at one offset
+        # modulo 4 KiB and load a fraction of the memory channels; the padding spreads them
+        if iso.ISO_OP_ALLTOALL in ops and p * (s * m + 128) <= (2 << 30):
+            ext = s * m + 128
+            sizes, displs = [m] * s, [i * m for i in range(s)]
+            psend = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(5)
+            precv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
+            wsb = iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m)
+            pwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+            r = iso.iso_neighbor_alltoallv_init(psend, sizes, displs, ext, precv, sizes, displs, ext, pwork, comm,
+                                                iso.ISO_ALG_COMBINED)
+            ms = time_steps([r], ksteps, 3) / ksteps
+            inf = iso.iso_request_info(r)
+            extras["alltoall_rows_padded_128B_combined"] = {
+                "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
+                "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1),
+                "frac_of_peak": round(2 * inf["bytes_read"] / ms / 1e6 / HBM_PEAK_GBS, 4), "launches": inf["launches"]}
+            iso.iso_request_free(r)
+            del psend, precv, pwork
+            torch.cuda.empty_cache()
         # the same torus taken as a box (no dimension wraps, Section 7): blocks whose source lies
         # outside stay untouched; moved bytes are nominal (every entry counted at every rank)
         if args.config == "2":
