@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--seed", type=int, default=2016)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparison algorithms and the copy ceiling")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="with --no-extras: still run the 1 GiB plain copy (calibration of the traffic counters)")
     ap.add_argument("--cpu-seconds", type=float, default=10.0)
     ap.add_argument("--small-sweep", action="store_true",
                     help="instead of the benchmark: all-to-all on tori of about 500 processes (the paper's own "
@@ -295,7 +297,26 @@ def main():
                      **{f"iso_neighbor_{op_name[op]}_init": round(t, 4) for op, t in zip(ops, t_init)}},
     }
 
+    def copy_reference_rate():
+        """GB/s read + written by the library's plain copy kernel on 1 GiB: the ceiling, and the
+        copy of known size that the HBM traffic counters are calibrated on."""
+        nb = 1 << 30
+        a = torch.empty(nb, dtype=torch.uint8, device=dev)
+        b = torch.empty(nb, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            iso.iso_copy_reference(a, b, nb, stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(20):
+            iso.iso_copy_reference(a, b, nb, stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
     # ---- comparison algorithms and the copy ceiling (not part of `value`) -------
+    if args.no_extras and args.copy_reference:
+        out["copy_1GiB_GBs_read_plus_write"] = copy_reference_rate()
     if not args.no_extras:
         extras = {}
         ksteps = max(5, K // 4)
@@ -322,20 +343,7 @@ def main():
                                     "moved_GBs": round(moved / ms / 1e6, 1), "launches": len(reqs)}
         for r in reqs:
             iso.iso_request_set_graph(r, False)
-        nb = 1 << 30
-        a = torch.empty(nb, dtype=torch.uint8, device=dev)
-        b = torch.empty(nb, dtype=torch.uint8, device=dev)
-        for _ in range(3):
-            iso.iso_copy_reference(a, b, nb, stream)
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(stream)
-        for _ in range(20):
-            iso.iso_copy_reference(a, b, nb, stream)
-        e1.record(stream)
-        torch.cuda.synchronize()
-        extras["copy_1GiB_GBs_read_plus_write"] = round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
-        del a, b
+        extras["copy_1GiB_GBs_read_plus_write"] = copy_reference_rate()
         # irregular all-to-all in the shape of the paper's stencil experiment (Section 4): block of
         # neighbour i has base^(d - ||C^i||_1) bytes; same torus, Moore radius 1, base 64
         if cfg.d == 3 and args.config == "2":
