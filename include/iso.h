@@ -40,8 +40,10 @@ enum iso_status {
     ISO_ERR_HIP       = 4,       /* a HIP runtime call failed (see iso_last_hip_error)      */
     ISO_ERR_NOMEM     = 5,       /* host allocation failed                                  */
     ISO_ERR_TOO_LARGE = 6,       /* a size exceeds what the kernels index (see iso_*_init)  */
-    ISO_ERR_POINTER   = 7        /* a buffer is not device memory or its allocation is too
+    ISO_ERR_POINTER   = 7,       /* a buffer is not device memory or its allocation is too
                                     small for the range the collective touches             */
+    ISO_ERR_SCRATCH   = 8        /* iso_neighbor_alltoall_noalloc: the collective needs more
+                                    than the library's static scratch memory holds         */
 };
 
 enum iso_op {
@@ -314,6 +316,32 @@ int iso_request_info(iso_request_t req, iso_request_info_t *info);
 /* Returns the plan the request executes (owned by the request; do not free). */
 int iso_request_plan(iso_request_t req, iso_plan_t *plan);
 int iso_request_free(iso_request_t *req);
+
+/* ---- for callers that cannot allocate device memory -------------------------
+ * Code under HIP graph capture, tight serving loops and harnesses that forbid
+ * hipMalloc cannot use the init calls (they allocate the request's device
+ * table) and may have no workspace to pass.  This call is
+ * iso_neighbor_alltoall_init + iso_start in one, with no request left behind:
+ * it enqueues one all-to-all (same arguments, layout [p][s][m], same result,
+ * same algorithms) on `hip_stream` and returns without waiting.  The table of
+ * block index maps and the intermediate buffer live in a static device array
+ * of ISO_NOALLOC_SCRATCH_BYTES that each GPU holds from the moment the
+ * library's code is loaded on it until the process ends; the table is written
+ * by small kernels that carry it in their arguments, ordered on the stream
+ * before the rounds.  No hipMalloc, hipFree, host-to-device copy or other
+ * allocating routine is called.
+ * Limits: the table (48 bytes per block-move per rank, plus 4*s*d) must fit
+ * ISO_NOALLOC_TABLE_BYTES and iso_workspace_bytes() the rest of the array,
+ * else ISO_ERR_SCRATCH and nothing is enqueued.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's
+ * contents (nothing in it needs to start at zero: every block of the
+ * intermediate buffer is written before it is read, and the table is rewritten
+ * by every call).  Calls follow each other safely on one stream; calls that
+ * overlap in time on one GPU (different streams, different threads) race. */
+#define ISO_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define ISO_NOALLOC_TABLE_BYTES   (256u << 10)
+int iso_neighbor_alltoall_noalloc(const void *sendbuf, void *recvbuf, size_t m, iso_comm_t comm,
+                                  int algorithm, void *hip_stream);
 
 /* ---- diagnostics ----------------------------------------------------------- */
 const char *iso_error_string(int status);

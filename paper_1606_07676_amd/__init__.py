@@ -12,7 +12,8 @@ from .binding import (  # noqa: F401
     ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR,
     ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR,
     ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP,
-    ISO_ERR_NOMEM, ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_MAX_DIMS,
+    ISO_ERR_NOMEM, ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_ERR_SCRATCH, ISO_MAX_DIMS,
+    ISO_NOALLOC_SCRATCH_BYTES, ISO_NOALLOC_TABLE_BYTES, iso_neighbor_alltoall_noalloc,
     Comm, Plan, Request,
     iso_neighborhood_create, iso_neighborhood_create_mesh, iso_neighborhood_info, iso_neighborhood_free,
     iso_plan_create, iso_plan_info, iso_plan_round, iso_plan_entries, iso_plan_free,

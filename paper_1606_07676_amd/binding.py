@@ -12,7 +12,8 @@ _lib = None
 
 ISO_MAX_DIMS = 16
 (ISO_SUCCESS, ISO_ERR_ARG, ISO_ERR_OVERLAP, ISO_ERR_WORKSPACE, ISO_ERR_HIP, ISO_ERR_NOMEM,
- ISO_ERR_TOO_LARGE, ISO_ERR_POINTER) = range(8)
+ ISO_ERR_TOO_LARGE, ISO_ERR_POINTER, ISO_ERR_SCRATCH) = range(9)
+ISO_NOALLOC_SCRATCH_BYTES, ISO_NOALLOC_TABLE_BYTES = 32 << 20, 256 << 10
 ISO_OP_ALLTOALL, ISO_OP_ALLGATHER = 0, 1
 ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP = 0, 1, 2, 3, 4
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
@@ -107,6 +108,7 @@ _PROTOTYPES = {
                                      ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgatherw_init": ([_VP, _SZ, _SZ, _VP, _VP, _VP, _SZ, _VP, _SZ, _VP, _I,
                                       ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_alltoall_noalloc": ([_VP, _VP, _SZ, _VP, _I, _VP], _I),
     "iso_start": ([_VP, _VP], _I),
     "iso_start_range": ([_VP, _I, _I, _VP], _I),
     "iso_request_set_graph": ([_VP, _I], _I),
@@ -428,6 +430,12 @@ def iso_neighbor_allgatherw_init(sendbuf, send_size, send_extent, recvbuf, recv_
                                  workspace_bytes=None):
     return _allgatherv("iso_neighbor_allgatherw_init", sendbuf, send_size, send_extent, recvbuf, recv_sizes,
                        recv_displs, recv_extent, workspace, comm, algorithm, workspace_bytes)
+
+
+def iso_neighbor_alltoall_noalloc(sendbuf, recvbuf, m, comm, algorithm=ISO_ALG_COMBINED, stream=None):
+    """One all-to-all enqueued on `stream` with no device allocation (see iso.h)."""
+    _check(load_library().iso_neighbor_alltoall_noalloc(_ptr(sendbuf), _ptr(recvbuf), m, comm.handle, algorithm,
+                                                        _stream_handle(stream)), "iso_neighbor_alltoall_noalloc")
 
 
 def iso_start(req, stream=None):

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -16,6 +17,12 @@
 namespace iso {
 thread_local int g_last_hip_error = 0;
 }
+
+// Device memory for iso_neighbor_alltoall_noalloc: the table of block index maps in the first
+// ISO_NOALLOC_TABLE_BYTES, the intermediate buffer of Algorithm 1 in the rest.  Every device the
+// library's code is loaded on holds its own copy until the process ends.  In host code the name
+// only stands for the symbol: the address on the current device comes from hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[ISO_NOALLOC_SCRATCH_BYTES];
 
 struct iso_comm_s {
     iso::Comm c;
@@ -211,6 +218,26 @@ int init_allgatherv(const void *sendbuf, size_t send_size, size_t send_extent, v
         if ((st = check_rows(lay.size, lay.recv_displ, recv_extent, true, lay.recv_span)) != ISO_SUCCESS) return st;
     }
     return make_request(ISO_OP_ALLGATHER, lay, sendbuf, recvbuf, workspace, workspace_bytes, comm, algorithm, req);
+}
+
+// Address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(unsigned char **out) {
+    int dev = -1;
+    ISO_HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return ISO_ERR_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        ISO_HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return ISO_ERR_HIP;
+        g_scratch_ptr[dev] = (unsigned char *)ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return ISO_SUCCESS;
 }
 
 }  // namespace
@@ -444,6 +471,29 @@ int iso_neighbor_allgatherw_init(const void *sendbuf, size_t send_size, size_t s
                                         recv_extent, workspace, workspace_bytes, comm, algorithm, req);
 }
 
+int iso_neighbor_alltoall_noalloc(const void *sendbuf, void *recvbuf, size_t m, iso_comm_t comm,
+                                  int algorithm, void *hip_stream) {
+    return guarded([&]() -> int {
+        if (!comm) return ISO_ERR_ARG;
+        const uint64_t p = (uint64_t)comm->c.p, s = (uint64_t)comm->c.s;
+        if (m && p > (~(uint64_t)0 >> 2) / std::max<uint64_t>(1, s) / m) return ISO_ERR_TOO_LARGE;
+        unsigned char *ptr = nullptr;
+        int st = scratch_of_current_device(&ptr);
+        if (st != ISO_SUCCESS) return st;
+        hipStream_t stream = (hipStream_t)hip_stream;
+        iso::BoundRequest b;
+        if ((st = iso::build_plan(comm->c, ISO_OP_ALLTOALL, algorithm, b.plan)) != ISO_SUCCESS) return st;
+        const iso::StaticArena arena{ptr, ISO_NOALLOC_TABLE_BYTES, stream};
+        st = iso::bind_request(b, comm->c, regular_layout(comm->c, ISO_OP_ALLTOALL, m), sendbuf, recvbuf,
+                               ptr + ISO_NOALLOC_TABLE_BYTES, ISO_NOALLOC_SCRATCH_BYTES - ISO_NOALLOC_TABLE_BYTES,
+                               &arena);
+        if (st != ISO_SUCCESS) return st;
+        for (const iso::Launch &l : b.launches)
+            if ((st = iso::enqueue(b.info.vector_bytes, l, stream)) != ISO_SUCCESS) return st;
+        return ISO_SUCCESS;
+    });
+}
+
 int iso_request_set_graph(iso_request_t req, int enable) {
     if (!req) return ISO_ERR_ARG;
     if (!enable || req->b.launches.empty()) {
@@ -564,6 +614,7 @@ const char *iso_error_string(int status) {
         case ISO_ERR_NOMEM: return "out of host memory";
         case ISO_ERR_TOO_LARGE: return "size exceeds the supported index range";
         case ISO_ERR_POINTER: return "buffer is not inside a device allocation of sufficient size";
+        case ISO_ERR_SCRATCH: return "collective needs more than the library's static scratch memory holds";
         default: return "unknown status";
     }
 }

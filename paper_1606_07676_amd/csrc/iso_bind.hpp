@@ -237,14 +237,45 @@ inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
 struct BoundRequest {
     Plan plan;
     iso_request_info_t info{};
-    void *dev_table = nullptr;
+    void *dev_table = nullptr;         // owned (hipMalloc) unless the request was bound to a StaticArena
     std::vector<Launch> launches;
 };
 
+// Device memory that the library already holds, for binding a schedule without allocating:
+// the table of block index maps goes to `table` (written by table_store_kernel launches on
+// `stream`, ordered before the rounds that read it), and the caller of bind_request passes the
+// rest of the arena as the workspace.  Nothing is allocated, copied or freed.
+struct StaticArena {
+    unsigned char *table;              // device address, 16-byte aligned
+    size_t table_bytes;
+    hipStream_t stream;
+};
+
+inline int store_table(const StaticArena &arena, size_t at, const void *host, size_t bytes) {
+    // `at` and `bytes` are multiples of 4: every part of the table is an array of 32-bit words or of DevEntry
+    const uint32_t *w = (const uint32_t *)host;
+    size_t words = bytes / 4, done = 0;
+    while (done < words) {
+        TableChunk ch;
+        ch.dst = (uint32_t *)(arena.table + at) + done;
+        ch.n = (uint32_t)std::min<size_t>(kStoreWords, words - done);
+        ch.reserved = 0;
+        std::memcpy(ch.words, w + done, (size_t)ch.n * 4);
+        hipLaunchKernelGGL(table_store_kernel, dim3((ch.n + kThreads - 1) / kThreads), dim3(kThreads), 0,
+                           arena.stream, ch);
+        ISO_HIP_TRY(hipGetLastError());
+        done += ch.n;
+    }
+    return ISO_SUCCESS;
+}
+
 // Checks the buffers, builds the device table and the launch list.  `rq.plan`
 // must already hold the schedule.
+// With `arena` the table is placed there instead of in an allocation of its own, and the workspace is
+// taken to be the library's own memory (no look-up of its allocation); ISO_ERR_SCRATCH if either does not fit.
 inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, const void *sendbuf,
-                        void *recvbuf, void *workspace, size_t workspace_bytes) {
+                        void *recvbuf, void *workspace, size_t workspace_bytes,
+                        const StaticArena *arena = nullptr) {
     const Plan &pl = rq.plan;
     const int op = pl.op;
     const uint64_t p = (uint64_t)c.p;
@@ -289,7 +320,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     if (send_len && !sendbuf) return ISO_ERR_ARG;
     if (recv_len && !recvbuf) return ISO_ERR_ARG;
     if (work_len && !workspace) return ISO_ERR_WORKSPACE;
-    if (work_len > workspace_bytes) return ISO_ERR_WORKSPACE;
+    if (work_len > workspace_bytes) return arena ? ISO_ERR_SCRATCH : ISO_ERR_WORKSPACE;
     const Range rs{(uintptr_t)sendbuf, send_len}, rr{(uintptr_t)recvbuf, recv_len},
         rw{(uintptr_t)workspace, work_len};
     if (overlap(rs, rr) || overlap(rs, rw) || overlap(rr, rw)) return ISO_ERR_OVERLAP;
@@ -300,7 +331,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     int st;
     if ((st = check_device_range(sendbuf, send_len)) != ISO_SUCCESS) return st;
     if ((st = check_device_range(recvbuf, recv_len)) != ISO_SUCCESS) return st;
-    if ((st = check_device_range(workspace, work_len)) != ISO_SUCCESS) return st;
+    if (!arena && (st = check_device_range(workspace, work_len)) != ISO_SUCCESS) return st;
 
     // address of rank 0's block and byte stride between ranks, per (buffer, slot)
     auto place = [&](int buf, int slot, uint64_t &addr, uint64_t &stride) {
@@ -493,17 +524,24 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     const size_t entry_bytes = table.size() * sizeof(DevEntry);
     const size_t off_bytes = c.can.size() * sizeof(uint32_t);
     const size_t pre_bytes = prefixes.size() * sizeof(uint32_t);
-    if (entry_bytes + off_bytes + pre_bytes) {
+    char *dev = nullptr;
+    if (arena) {
+        if (entry_bytes + off_bytes + pre_bytes > arena->table_bytes) return ISO_ERR_SCRATCH;
+        dev = (char *)arena->table;
+        if ((st = store_table(*arena, 0, table.data(), entry_bytes)) != ISO_SUCCESS) return st;
+        if ((st = store_table(*arena, entry_bytes, c.can.data(), off_bytes)) != ISO_SUCCESS) return st;
+        if ((st = store_table(*arena, entry_bytes + off_bytes, prefixes.data(), pre_bytes)) != ISO_SUCCESS) return st;
+    } else if (entry_bytes + off_bytes + pre_bytes) {
         ISO_HIP_TRY(hipMalloc(&rq.dev_table, entry_bytes + off_bytes + pre_bytes));
-        char *d = (char *)rq.dev_table;
-        if (entry_bytes) ISO_HIP_TRY(hipMemcpy(d, table.data(), entry_bytes, hipMemcpyHostToDevice));
-        if (off_bytes) ISO_HIP_TRY(hipMemcpy(d + entry_bytes, c.can.data(), off_bytes, hipMemcpyHostToDevice));
+        dev = (char *)rq.dev_table;
+        if (entry_bytes) ISO_HIP_TRY(hipMemcpy(dev, table.data(), entry_bytes, hipMemcpyHostToDevice));
+        if (off_bytes) ISO_HIP_TRY(hipMemcpy(dev + entry_bytes, c.can.data(), off_bytes, hipMemcpyHostToDevice));
         if (pre_bytes)
-            ISO_HIP_TRY(hipMemcpy(d + entry_bytes + off_bytes, prefixes.data(), pre_bytes, hipMemcpyHostToDevice));
+            ISO_HIP_TRY(hipMemcpy(dev + entry_bytes + off_bytes, prefixes.data(), pre_bytes, hipMemcpyHostToDevice));
     }
-    const DevEntry *dev_entries = (const DevEntry *)rq.dev_table;
-    const uint32_t *dev_offsets = (const uint32_t *)((char *)rq.dev_table + entry_bytes);
-    const uint32_t *dev_prefix = (const uint32_t *)((char *)rq.dev_table + entry_bytes + off_bytes);
+    const DevEntry *dev_entries = (const DevEntry *)dev;
+    const uint32_t *dev_offsets = (const uint32_t *)(dev + entry_bytes);
+    const uint32_t *dev_prefix = (const uint32_t *)(dev + entry_bytes + off_bytes);
     for (Pending &pd : pending) {
         if (pd.l.kernel == kVectorKernel) {
             pd.l.vec.entries = dev_entries + pd.first_entry;

@@ -481,4 +481,20 @@ __global__ __launch_bounds__(kThreads) void copy_kernel(const V *__restrict__ sr
     if (u < n_units) __builtin_nontemporal_store(__builtin_nontemporal_load(src + u), dst + u);
 }
 
+// Writes up to kStoreWords 32-bit words, carried in the kernel's own arguments, to device
+// memory: how a table of block index maps reaches the device when the host may neither
+// allocate nor copy (the launch itself is the transfer, and it is ordered by the stream).
+constexpr uint32_t kStoreWords = 768;
+struct TableChunk {
+    uint32_t *dst;
+    uint32_t n;            // words to write, at most kStoreWords
+    uint32_t reserved;
+    uint32_t words[kStoreWords];
+};
+
+__global__ __launch_bounds__(kThreads) void table_store_kernel(const TableChunk c) {
+    const uint32_t i = blockIdx.x * (uint32_t)kThreads + threadIdx.x;
+    if (i < c.n) c.dst[i] = c.words[i];
+}
+
 }  // namespace iso

@@ -50,7 +50,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_error_strings_and_bad_arguments():
     assert iso.iso_error_string(0) == "success"
-    for code in range(1, 8):
+    for code in range(1, 9):
         assert iso.iso_error_string(code) not in ("success", "unknown status")
     with pytest.raises(iso.IsoError) as e:
         iso.iso_neighborhood_create([4, 0], [(1, 1)])
