@@ -1,14 +1,21 @@
 #!/usr/bin/env python3
 """Benchmark of the hot path on one MI355X: persistent isomorphic all-to-all and
 allgather with the message-combining (torus-direct) schedule, one kernel per
-round, on a synthetic workload held entirely in HBM.
+round, on synthetic workloads held entirely in HBM.
 
-One step = one iso_start of every collective the workload names (config 2:
+One step = one iso_start of every collective the workload names (e.g. config 5:
 all-to-all, then allgather), enqueued back to back on one stream.  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line on stdout;
 everything else goes to stderr.
+
+Default run: the headline numbers (`value`, `roofline`, `cpu_baseline`) are taken on
+the largest workload, config 5 (8^5 torus, 40 neighbours, 4 KiB blocks, 5.4 GB per
+buffer); the other workloads whose blocks are at least 128 bytes (configs 2, 3 and
+4) are timed the same way in the same run and reported under `workloads`, each with
+its own roofline and CPU baseline.  `--config N` times one workload only.
 """
 import argparse
+import glob
 import json
 import os
 import sys
@@ -19,6 +26,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak, GB/s
+LAST_LEVEL_CACHE_BYTES = 256 << 20
+METRIC = "delivered GB/s (p*s*m bytes per collective / time) at 1 GPU; % of HBM peak"
 
 
 def log(*a):
@@ -28,34 +37,43 @@ def log(*a):
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="2", help="workload: 1..5 (default 2, the one the metric is quoted on)")
-    ap.add_argument("--m", type=int, default=None, help="override the block size in bytes")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default=None,
+                    help="time only this workload (1..5); default: config 5 as the headline, then 2, 3 and 4")
+    ap.add_argument("--m", type=int, default=None, help="override the block size in bytes (with --config)")
     ap.add_argument("--layout", choices=("rank", "slot"), default="rank",
                     help="buffers of the timed requests: rank = the paper's [p][s][m] (default), slot = [s][p][m]")
+    ap.add_argument("--algorithm", choices=("combined", "bydim", "sx_fused", "sx_rounds", "onehop"),
+                    default="combined", help="algorithm of the timed requests (default: combined, one kernel per round)")
+    ap.add_argument("--pad", type=int, default=0,
+                    help="all-to-all only: every rank's row padded by this many bytes (irregular interface, equal blocks)")
+    ap.add_argument("--mesh", action="store_true", help="the torus taken as a box: no dimension wraps (Section 7)")
+    ap.add_argument("--irregular", type=int, default=0, metavar="BASE",
+                    help="all-to-all with the stencil block sizes of Section 4: BASE^(d - |C|_1) bytes per neighbour")
+    ap.add_argument("--graph", action="store_true", help="replay the timed requests as HIP graphs")
     ap.add_argument("--seed", type=int, default=2016)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparison algorithms and the copy ceiling")
+    ap.add_argument("--timed-only", action="store_true",
+                    help="only the timed region: no isolated repetitions, no per-round timing (for counter runs)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="with --no-extras: still run the 1 GiB plain copy (calibration of the traffic counters)")
-    ap.add_argument("--cpu-seconds", type=float, default=10.0)
+    ap.add_argument("--cpu-seconds", type=float, default=6.0, help="CPU-oracle timing budget per workload")
     ap.add_argument("--small-sweep", action="store_true",
                     help="instead of the benchmark: all-to-all on tori of about 500 processes (the paper's own "
                          "regime, Section 4), every algorithm, three block sizes; prints one JSON line")
     return ap.parse_args()
 
 
-def recorded_traffic(cfg_name, m):
-    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
-    runs of this same command (counters cannot be read from inside the process).
-    Only the workload the summary was taken on gets a value; anything else: None."""
-    path = os.path.join(ROOT, "profiles", "shift_round_kernel_c2_hbm_traffic.txt")
-    if not (cfg_name.startswith("c2_") and m == 256 and os.path.exists(path)):
-        return None
-    for line in open(path):
-        if line.startswith("traffic_bytes_per_launch"):
-            return int(line.split("=")[1])
+def recorded_traffic(tag):
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summaries of
+    this same command (counters cannot be read from inside the process): the value of the
+    summary whose name carries `tag`, else None."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"*{tag}_hbm_traffic.txt"))):
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return int(line.split("=")[1])
     return None
 
 
@@ -94,90 +112,140 @@ def small_sweep():
                 wsb = iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, m)
                 work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                 req = iso.iso_neighbor_alltoall_init(send, recv, m, work, comm, alg)
-                for _ in range(10):
-                    iso.iso_start(req, stream)
-                torch.cuda.synchronize()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record(stream)
-                for _ in range(200):
-                    iso.iso_start(req, stream)
-                e1.record(stream)
-                torch.cuda.synchronize()
-                row[an] = {"us": round(e0.elapsed_time(e1) / 200 * 1e3, 2),
-                           "launches": iso.iso_request_info(req)["launches"]}
+                for graph in (False, True):
+                    iso.iso_request_set_graph(req, graph)
+                    for _ in range(10):
+                        iso.iso_start(req, stream)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                    for _ in range(200):
+                        iso.iso_start(req, stream)
+                    e1.record(stream)
+                    torch.cuda.synchronize()
+                    if graph:
+                        row[an]["graph_us"] = round(e0.elapsed_time(e1) / 200 * 1e3, 2)
+                    else:
+                        row[an] = {"us": round(e0.elapsed_time(e1) / 200 * 1e3, 2),
+                                   "launches": iso.iso_request_info(req)["launches"]}
                 iso.iso_request_free(req)
             log(row)
             rows.append(row)
     print(json.dumps({"small_sweep": rows}), flush=True)
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        log("bench.py: this build runs on ONE GPU (all p virtual ranks live in one device's HBM); "
-            "--gpus must be 1.")
-        sys.exit(2)
+class Bench:
+    """One workload on the device: buffers, requests, timing, the CPU-oracle leg."""
+    host_threads = 0           # threads the C oracle used on its first (default) call
 
-    import numpy as np
-    import torch
-    import iso_inputs as gen
-    import paper_1606_07676_amd as iso
+    def __init__(self, args, cfg, m):
+        import numpy as np
+        import torch
+        import iso_inputs as gen
+        import paper_1606_07676_amd as iso
+        self.np, self.torch, self.gen, self.iso = np, torch, gen, iso
+        self.args, self.cfg, self.m = args, cfg, m
+        self.dev = "cuda:0"
+        self.stream = torch.cuda.current_stream()
+        self.p, self.s = cfg.p, cfg.s
+        self.slot = args.layout == "slot"
+        self.alg = {"combined": iso.ISO_ALG_COMBINED, "bydim": iso.ISO_ALG_COMBINED_BYDIM,
+                    "sx_fused": iso.ISO_ALG_SX_FUSED, "sx_rounds": iso.ISO_ALG_SX_ROUNDS,
+                    "onehop": iso.ISO_ALG_ONEHOP}[args.algorithm]
+        self.plain = not (args.mesh or args.irregular or args.pad)      # the CPU leg covers these only
+        self.op_name = {iso.ISO_OP_ALLTOALL: "alltoall", iso.ISO_OP_ALLGATHER: "allgather"}
+        self.ops = [iso.ISO_OP_ALLTOALL if o == "alltoall" else iso.ISO_OP_ALLGATHER for o in cfg.ops]
+        if not self.plain:
+            self.ops = [iso.ISO_OP_ALLTOALL]
+        self.keep = []
 
-    if not torch.cuda.is_available():
-        log("bench.py: no GPU visible")
-        sys.exit(1)
-    if args.small_sweep:
-        small_sweep()
-        return
-    iso.load_library()
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = gen.get_config(args.config)
-    m = args.m or cfg.m
-    p, s = cfg.p, cfg.s
-    K, W = args.steps, args.warmup
-    stream = torch.cuda.current_stream()
-    log(f"workload {cfg.name}: dims={cfg.dims} p={p} s={s} m={m} ops={cfg.ops}")
-
-    # ---- set-up (host side of the hot path: neighbourhood, schedules, binding) ----
-    t0 = time.perf_counter()
-    comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
-    t_create = (time.perf_counter() - t0) * 1e3
-    cinfo = iso.iso_neighborhood_info(comm)
-
-    ops = [iso.ISO_OP_ALLTOALL if o == "alltoall" else iso.ISO_OP_ALLGATHER for o in cfg.ops]
-    op_name = {iso.ISO_OP_ALLTOALL: "alltoall", iso.ISO_OP_ALLGATHER: "allgather"}
-    bufs = {}
-    for op in ops:
-        if op == iso.ISO_OP_ALLTOALL:
-            send = gen.alltoall_send_torch(args.seed, p, s, m, cfg.kind, device=dev)
+        t0 = time.perf_counter()
+        if args.mesh:
+            self.comm = iso.iso_neighborhood_create_mesh(cfg.dims, (0,) * cfg.d, cfg.offsets)
         else:
-            send = gen.allgather_send_torch(args.seed, p, m, cfg.kind, device=dev)
-        recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=dev)
-        bufs[op] = (send, recv)
-    # buffers of the timed requests; with --layout slot the same blocks as [s][p][m]
-    slot = args.layout == "slot"
-    timed = {}
-    for op in ops:
-        send, recv = bufs[op]
-        if slot:
-            tsend = send.permute(1, 0, 2).contiguous() if op == iso.ISO_OP_ALLTOALL else send
-            timed[op] = (tsend, torch.full((s, p, m), 0xEE, dtype=torch.uint8, device=dev))
-        else:
-            timed[op] = (send, recv)
+            self.comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
+        self.t_create = (time.perf_counter() - t0) * 1e3
+        self.cinfo = iso.iso_neighborhood_info(self.comm)
 
-    def make_request(op, alg, timed_buffers=False):
-        send, recv = timed[op] if timed_buffers else bufs[op]
-        wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+        p, s, dev = self.p, self.s, self.dev
+        self.bufs, self.timed = {}, {}
+        if self.plain:
+            for op in self.ops:
+                if op == iso.ISO_OP_ALLTOALL:
+                    send = gen.alltoall_send_torch(args.seed, p, s, m, cfg.kind, device=dev)
+                else:
+                    send = gen.allgather_send_torch(args.seed, p, m, cfg.kind, device=dev)
+                recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=dev)
+                self.bufs[op] = (send, recv)
+            for op in self.ops:               # with --layout slot the same blocks as [s][p][m]
+                send, recv = self.bufs[op]
+                if self.slot:
+                    tsend = send.permute(1, 0, 2).contiguous() if op == iso.ISO_OP_ALLTOALL else send
+                    self.timed[op] = (tsend, torch.full((s, p, m), 0xEE, dtype=torch.uint8, device=dev))
+                else:
+                    self.timed[op] = (send, recv)
+        self.footprint = 0
+        self.reqs, self.t_init = [], []
+        for op in self.ops:
+            r, t = self.make_request(op, self.alg, timed_buffers=True)
+            self.reqs.append(r)
+            self.t_init.append(t)
+        self.infos = [iso.iso_request_info(r) for r in self.reqs]
+        self.delivered = sum(i["delivered_bytes"] for i in self.infos)
+        self.moved = sum(i["bytes_read"] + i["bytes_written"] for i in self.infos)
+        self.launches = sum(i["launches"] for i in self.infos)
+        if args.graph:
+            for r in self.reqs:
+                iso.iso_request_set_graph(r, True)
+
+    # -- requests ------------------------------------------------------------------
+    def make_request(self, op, alg, timed_buffers=False):
+        iso, torch, gen, args = self.iso, self.torch, self.gen, self.args
+        p, s, m, dev = self.p, self.s, self.m, self.dev
+        if not self.plain:                                 # irregular interface: padded rows or stencil sizes
+            if args.irregular:
+                sizes = gen.stencil_block_sizes(self.cfg.offsets, args.irregular)
+                displs, ext = gen.packed_displacements(sizes, 16)
+            else:
+                sizes, displs, ext = [m] * s, [i * m for i in range(s)], s * m
+            ext += args.pad
+            wsb = iso.iso_workspace_bytes_v(self.comm, op, alg, sizes)
+            work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
+            if self.slot:
+                pd, at = [], 0
+                for sz in sizes:
+                    pd.append(at)
+                    at += -(-p * sz // 16) * 16
+                send = torch.empty(at, dtype=torch.uint8, device=dev).fill_(3)
+                recv = torch.empty(at, dtype=torch.uint8, device=dev)
+                t = time.perf_counter()
+                req = iso.iso_neighbor_alltoallv_init_layout(send, sizes, pd, 0, recv, sizes, pd, 0,
+                                                             iso.ISO_LAYOUT_SLOT_MAJOR, work, self.comm, alg)
+            else:
+                send = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
+                recv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
+                t = time.perf_counter()
+                req = iso.iso_neighbor_alltoallv_init(send, sizes, displs, ext, recv, sizes, displs, ext,
+                                                      work, self.comm, alg)
+            dt = (time.perf_counter() - t) * 1e3
+            self.keep += [send, recv, work]
+            self.footprint += send.numel() + recv.numel() + wsb
+            return req, dt
+        send, recv = self.timed[op] if timed_buffers else self.bufs[op]
+        wsb = iso.iso_workspace_bytes(self.comm, op, alg, m)
         work = torch.empty(wsb, dtype=torch.uint8, device=dev) if wsb else None
         init = iso.iso_neighbor_alltoall_init_layout if op == iso.ISO_OP_ALLTOALL else \
             iso.iso_neighbor_allgather_init_layout
-        layout = iso.ISO_LAYOUT_SLOT_MAJOR if (timed_buffers and slot) else iso.ISO_LAYOUT_RANK_MAJOR
+        layout = iso.ISO_LAYOUT_SLOT_MAJOR if (timed_buffers and self.slot) else iso.ISO_LAYOUT_RANK_MAJOR
         t = time.perf_counter()
-        req = init(send, recv, m, layout, work, comm, alg)
-        return req, (time.perf_counter() - t) * 1e3
+        req = init(send, recv, m, layout, work, self.comm, alg)
+        dt = (time.perf_counter() - t) * 1e3
+        if timed_buffers:
+            self.footprint += send.numel() + recv.numel() + wsb
+        return req, dt
 
-    def time_steps(reqs, steps, warmup):
+    def time_steps(self, reqs, steps, warmup):
+        iso, torch, stream = self.iso, self.torch, self.stream
         for _ in range(warmup):
             for r in reqs:
                 iso.iso_start(r, stream)
@@ -191,118 +259,141 @@ def main():
         torch.cuda.synchronize()
         return e0.elapsed_time(e1)                         # ms for `steps` steps
 
-    reqs, t_init = [], []
-    for op in ops:
-        r, t = make_request(op, iso.ISO_ALG_COMBINED, timed_buffers=True)
-        reqs.append(r)
-        t_init.append(t)
-    infos = [iso.iso_request_info(r) for r in reqs]
-    delivered = sum(i["delivered_bytes"] for i in infos)
-    moved = sum(i["bytes_read"] + i["bytes_written"] for i in infos)
-    launches = sum(i["launches"] for i in infos)
+    # -- the timed region and what is derived from it ---------------------------------
+    def run(self):
+        iso, torch, args, cfg = self.iso, self.torch, self.args, self.cfg
+        K, W, m, p, s = args.steps, args.warmup, self.m, self.p, self.s
+        reqs, infos, stream = self.reqs, self.infos, self.stream
+        log(f"workload {cfg.name}: dims={cfg.dims} p={p} s={s} m={m} ops={[self.op_name[o] for o in self.ops]} "
+            f"algorithm={args.algorithm} layout={args.layout}")
+        total_ms = self.time_steps(reqs, K, W)
+        ms_per_step = total_ms / K
+        value = self.delivered / (ms_per_step * 1e-3) / 1e9
+        log(f"  {ms_per_step:.4f} ms/step, delivered {value:.1f} GB/s, moved "
+            f"{self.moved / (ms_per_step * 1e-3) / 1e9:.1f} GB/s over {self.launches} launches")
 
-    # ---- the timed region ------------------------------------------------------
-    total_ms = time_steps(reqs, K, W)
-    ms_per_step = total_ms / K
-    value = delivered / (ms_per_step * 1e-3) / 1e9
-    log(f"combined: {ms_per_step:.4f} ms/step, delivered {value:.1f} GB/s, moved "
-        f"{moved / (ms_per_step * 1e-3) / 1e9:.1f} GB/s over {launches} launches")
-
-    # ---- the paper's measurement protocol (Section 4): every repetition timed on its own
-    # after a synchronisation, outliers outside [Q1 - 3 IQR, Q3 + 3 IQR] dropped, median kept
-    reps = 100
-    rep_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for a, b in rep_ev:
+        # the paper's measurement protocol (Section 4): every repetition timed on its own after a
+        # synchronisation, outliers outside [Q1 - 3 IQR, Q3 + 3 IQR] dropped, median kept
+        reps = 0 if args.timed_only else 100
+        rep_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for a, b in rep_ev:
+            torch.cuda.synchronize()
+            a.record(stream)
+            for r in reqs:
+                iso.iso_start(r, stream)
+            b.record(stream)
         torch.cuda.synchronize()
-        a.record(stream)
-        for r in reqs:
-            iso.iso_start(r, stream)
-        b.record(stream)
-    torch.cuda.synchronize()
-    rep_ms = sorted(a.elapsed_time(b) for a, b in rep_ev)
-    q1, q3 = rep_ms[reps // 4], rep_ms[(3 * reps) // 4]
-    kept = [t for t in rep_ms if q1 - 3 * (q3 - q1) <= t <= q3 + 3 * (q3 - q1)]
-    protocol = {"repetitions": reps, "kept_after_tukey_3iqr": len(kept), "median_ms": round(median(kept), 5),
-                "min_ms": round(kept[0], 5), "max_ms": round(kept[-1], 5),
-                "delivered_GBs_at_median": round(delivered / median(kept) / 1e6, 1)}
+        protocol = None
+        if reps:
+            rep_ms = sorted(a.elapsed_time(b) for a, b in rep_ev)
+            q1, q3 = rep_ms[reps // 4], rep_ms[(3 * reps) // 4]
+            kept = [t for t in rep_ms if q1 - 3 * (q3 - q1) <= t <= q3 + 3 * (q3 - q1)]
+            protocol = {"repetitions": reps, "kept_after_tukey_3iqr": len(kept), "median_ms": round(median(kept), 5),
+                        "min_ms": round(kept[0], 5), "max_ms": round(kept[-1], 5),
+                        "delivered_GBs_at_median": round(self.delivered / median(kept) / 1e6, 1)}
 
-    # ---- per-launch durations of the round kernel (HIP events on the launch stream) ----
-    per_round = []
-    ev_steps = max(1, min(K, 50))
-    for r, inf in zip(reqs, infos):
-        plan = iso.iso_request_plan(r)
-        n = inf["launches"]
-        ks = [iso.iso_plan_round(plan, q)["n_entries"] for q in range(n)]
-        dims_ = [iso.iso_plan_round(plan, q)["dim"] for q in range(n)]
-        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                for _ in range(n)] for _ in range(ev_steps)]
-        torch.cuda.synchronize()
-        for st in range(ev_steps):
+        # per-launch durations (HIP events on the launch stream around single launches; these
+        # include the event markers themselves and are listed for orientation)
+        per_round = []
+        ev_steps = max(1, min(K, 30))
+        for r, inf in zip(reqs, infos):
+            if args.timed_only:
+                break
+            plan = iso.iso_request_plan(r)
+            n = inf["launches"]
+            n_rounds = iso.iso_plan_info(plan)["launches"]
+            if n != n_rounds:          # a round was split over several launches: no per-round listing
+                continue
+            ks = [iso.iso_plan_round(plan, q)["n_entries"] for q in range(n)]
+            dims_ = [iso.iso_plan_round(plan, q)["dim"] for q in range(n)]
+            evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                    for _ in range(n)] for _ in range(ev_steps)]
+            torch.cuda.synchronize()
+            for st in range(ev_steps):
+                for q in range(n):
+                    a, b = evs[st][q]
+                    a.record(stream)
+                    iso.iso_start_range(r, q, 1, stream)
+                    b.record(stream)
+            torch.cuda.synchronize()
+            uniform = not args.irregular
             for q in range(n):
-                a, b = evs[st][q]
-                a.record(stream)
-                iso.iso_start_range(r, q, 1, stream)
-                b.record(stream)
-        torch.cuda.synchronize()
-        for q in range(n):
-            t_ms = median([evs[st][q][0].elapsed_time(evs[st][q][1]) for st in range(ev_steps)])
-            nbytes = 2 * ks[q] * p * m
-            per_round.append({"op": op_name[inf["op"]], "round": q, "dim": dims_[q], "k": ks[q],
-                              "us": round(t_ms * 1e3, 2), "moved_GBs": round(nbytes / (t_ms * 1e-3) / 1e9, 1)})
-    # Every launch of the step is the same kernel (shift_round_kernel, 16-byte units), so its
-    # average launch duration over the timed region is region time / launches in the region.
-    # This includes the gaps between back-to-back launches (the per-round event pairs above
-    # additionally include the event markers themselves and are listed for orientation only).
-    alg_bytes_per_launch = moved / launches
-    avg_launch_ms = ms_per_step / launches
-    achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
-    roofline = {
-        "kernel": "shift_round_kernel<16B>",
-        "bound": "hbm",
-        "achieved": round(achieved, 1),
-        "peak": HBM_PEAK_GBS,
-        "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4),
-        "traffic": None if slot else recorded_traffic(cfg.name, m),
-        "algorithmic_bytes_per_launch": int(alg_bytes_per_launch),
-        "avg_launch_us": round(avg_launch_ms * 1e3, 2),
-        "launches_per_step": launches,
-    }
+                t_ms = median([evs[st][q][0].elapsed_time(evs[st][q][1]) for st in range(ev_steps)])
+                row = {"op": self.op_name[inf["op"]], "round": q, "dim": dims_[q], "k": ks[q],
+                       "us": round(t_ms * 1e3, 2)}
+                if uniform:
+                    row["moved_GBs"] = round(2 * ks[q] * p * m / (t_ms * 1e-3) / 1e9, 1)
+                per_round.append(row)
 
-    out = {
-        "metric": "delivered GB/s (p*s*m bytes per collective / time) at 1 GPU; % of HBM peak",
-        "value": round(value, 2),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": K,
-        "warmup": W,
-        "ms_per_step": round(ms_per_step, 5),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "u8",
-        "data": "synthetic",
-        "config": {
-            "workload": f"{cfg.name}: torus {'x'.join(map(str, cfg.dims))} (p={p}), s={s}, m={m} B, "
-                        f"{'+'.join(cfg.ops)} per step, message-combining schedule, one kernel per round",
-            "layout": "[s][p][m] (slot-major)" if slot else "[p][s][m] (rank-major, the paper's)",
-            "algorithm": "combined (torus-direct)", "seed": args.seed,
-            "rounds": cinfo["rounds"], "delivered_bytes_per_step": delivered, "moved_bytes_per_step": moved,
-        },
-        "verified_against_oracle": None,      # set by the CPU-oracle leg below
-        "roofline": roofline,
-        "isolated_repetitions": protocol,
-        "per_round": per_round,
-        "setup_ms": {"iso_neighborhood_create": round(t_create, 4),
-                     **{f"iso_neighbor_{op_name[op]}_init": round(t, 4) for op, t in zip(ops, t_init)}},
-    }
+        # Every launch of the step is the same kernel, so its average launch duration over the
+        # timed region is region time / launches in the region (gaps between back-to-back
+        # launches included).
+        alg_bytes_per_launch = self.moved / self.launches
+        avg_launch_ms = ms_per_step / self.launches
+        achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
+        kernel = ("vector_round_kernel" if args.algorithm.startswith("sx") else
+                  "block_round_kernel" if args.irregular else
+                  "mesh_shift_round_kernel" if args.mesh else "shift_round_kernel") + "<16B>"
+        tag = self.tag()
+        roofline = {
+            "kernel": kernel, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": recorded_traffic(tag),
+            "algorithmic_bytes_per_launch": int(alg_bytes_per_launch),
+            "avg_launch_us": round(avg_launch_ms * 1e3, 2), "launches_per_step": self.launches,
+        }
+        out = {
+            "value": round(value, 2), "unit": "GB/s", "ms_per_step": round(ms_per_step, 5),
+            "config": {
+                "workload": f"{cfg.name if m == cfg.m else cfg.name.rsplit('_m', 1)[0] + f'_m{m}'}: torus "
+                            f"{'x'.join(map(str, cfg.dims))} (p={p}), s={s}, m={m} B, "
+                            f"{'+'.join(self.op_name[o] for o in self.ops)} per step, "
+                            + ("message-combining schedule, one kernel per round" if args.algorithm == "combined"
+                               else f"algorithm {args.algorithm}"),
+                "layout": "[s][p][m] (slot-major)" if self.slot else "[p][s][m] (rank-major, the paper's)",
+                "algorithm": args.algorithm, "seed": args.seed, "profile_tag": tag,
+                "rounds": self.cinfo["rounds"], "delivered_bytes_per_step": self.delivered,
+                "moved_bytes_per_step": self.moved,
+                "device_footprint_bytes": int(self.footprint),
+                "exceeds_last_level_cache": bool(self.footprint > LAST_LEVEL_CACHE_BYTES),
+            },
+            "verified_against_oracle": None,      # set by the CPU-oracle leg
+            "roofline": roofline,
+            "isolated_repetitions": protocol,
+            "per_round": per_round,
+            "setup_ms": {"iso_neighborhood_create": round(self.t_create, 4),
+                         **{f"iso_neighbor_{self.op_name[op]}_init": round(t, 4)
+                            for op, t in zip(self.ops, self.t_init)}},
+        }
+        for key, flag in (("mesh", args.mesh), ("irregular_base", args.irregular), ("row_padding", args.pad),
+                          ("graph", args.graph)):
+            if flag:
+                out["config"][key] = flag
+        return out
 
-    def copy_reference_rate():
+    def tag(self):
+        """Names the (workload, variant) in the file names under profiles/."""
+        a = self.args
+        t = f"c{self.gen.CONFIGS.index(self.cfg) + 1}_m{self.m}"
+        if a.algorithm != "combined":
+            t += f"_{a.algorithm}"
+        if self.slot:
+            t += "_slot"
+        if a.mesh:
+            t += "_mesh"
+        if a.irregular:
+            t += f"_stencil{a.irregular}"
+        if a.pad:
+            t += f"_pad{a.pad}"
+        return t
+
+    def copy_reference_rate(self):
         """GB/s read + written by the library's plain copy kernel on 1 GiB: the ceiling, and the
         copy of known size that the HBM traffic counters are calibrated on."""
+        iso, torch, stream = self.iso, self.torch, self.stream
         nb = 1 << 30
-        a = torch.empty(nb, dtype=torch.uint8, device=dev)
-        b = torch.empty(nb, dtype=torch.uint8, device=dev)
+        a = torch.empty(nb, dtype=torch.uint8, device=self.dev)
+        b = torch.empty(nb, dtype=torch.uint8, device=self.dev)
         for _ in range(3):
             iso.iso_copy_reference(a, b, nb, stream)
         torch.cuda.synchronize()
@@ -314,39 +405,51 @@ def main():
         torch.cuda.synchronize()
         return round(2 * nb * 20 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
 
-    # ---- comparison algorithms and the copy ceiling (not part of `value`) -------
-    if args.no_extras and args.copy_reference:
-        out["copy_1GiB_GBs_read_plus_write"] = copy_reference_rate()
-    if not args.no_extras:
+    # -- comparison algorithms (not part of `value`) ------------------------------------
+    def comparison(self):
+        iso, torch, gen, args, cfg = self.iso, self.torch, self.gen, self.args, self.cfg
+        p, s, m, dev, ops, comm = self.p, self.s, self.m, self.dev, self.ops, self.comm
+        K = args.steps
         extras = {}
         ksteps = max(5, K // 4)
+
+        def rate(rs, ms, hbm_label=True):
+            """`moved_GBs` counts the bytes the algorithm asks for (read + written), which is
+            what HBM carries for the message-combining schedules (every block is read once and
+            written once per hop).  The s-exchange allgather reads each source block s times,
+            mostly from cache, so for it the figure is not HBM traffic and gets no fraction."""
+            mv = sum(iso.iso_request_info(r)["bytes_read"] * 2 for r in rs)
+            dl = sum(iso.iso_request_info(r)["delivered_bytes"] for r in rs)
+            d = {"ms_per_step": round(ms, 5), "delivered_GBs": round(dl / ms / 1e6, 1),
+                 "launches": sum(iso.iso_request_info(r)["launches"] for r in rs)}
+            if hbm_label:
+                d["moved_GBs"] = round(mv / ms / 1e6, 1)
+                d["frac_of_peak"] = round(mv / ms / 1e6 / HBM_PEAK_GBS, 4)
+            else:
+                d["requested_GBs_not_hbm"] = round(mv / ms / 1e6, 1)
+            return d
+
         for name, alg in (("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM), ("sx_fused", iso.ISO_ALG_SX_FUSED),
                           ("sx_rounds", iso.ISO_ALG_SX_ROUNDS), ("onehop", iso.ISO_ALG_ONEHOP)):
-            rs = [make_request(op, alg)[0] for op in ops]
-            ms = time_steps(rs, ksteps, 3) / ksteps
-            mv = sum(iso.iso_request_info(r)["bytes_read"] * 2 for r in rs)
-            extras[name] = {"ms_per_step": round(ms, 5), "delivered_GBs": round(delivered / ms / 1e6, 1),
-                            "moved_GBs": round(mv / ms / 1e6, 1),
-                            "launches": sum(iso.iso_request_info(r)["launches"] for r in rs)}
+            rs = [self.make_request(op, alg)[0] for op in ops]
+            ms = self.time_steps(rs, ksteps, 3) / ksteps
+            extras[name] = rate(rs, ms, hbm_label=not (name.startswith("sx") and iso.ISO_OP_ALLGATHER in ops))
             for r in rs:
                 iso.iso_request_free(r)
-        for op, r in zip(ops, reqs):
-            ms = time_steps([r], ksteps, 3) / ksteps
-            inf = iso.iso_request_info(r)
-            extras[f"combined_{op_name[op]}_only"] = {
-                "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
-                "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
-        for r in reqs:                                  # the same requests replayed as HIP graphs
+        for op, r in zip(ops, self.reqs):
+            ms = self.time_steps([r], ksteps, 3) / ksteps
+            extras[f"combined_{self.op_name[op]}_only"] = rate([r], ms)
+        for r in self.reqs:                                  # the same requests replayed as HIP graphs
             iso.iso_request_set_graph(r, True)
-        ms = time_steps(reqs, ksteps, 3) / ksteps
-        extras["combined_graph"] = {"ms_per_step": round(ms, 5), "delivered_GBs": round(delivered / ms / 1e6, 1),
-                                    "moved_GBs": round(moved / ms / 1e6, 1), "launches": len(reqs)}
-        for r in reqs:
+        ms = self.time_steps(self.reqs, ksteps, 3) / ksteps
+        extras["combined_graph"] = rate(self.reqs, ms)
+        extras["combined_graph"]["launches"] = len(self.reqs)
+        for r in self.reqs:
             iso.iso_request_set_graph(r, False)
-        extras["copy_1GiB_GBs_read_plus_write"] = copy_reference_rate()
+        extras["copy_1GiB_GBs_read_plus_write"] = self.copy_reference_rate()
         # irregular all-to-all in the shape of the paper's stencil experiment (Section 4): block of
         # neighbour i has base^(d - ||C^i||_1) bytes; same torus, Moore radius 1, base 64
-        if cfg.d == 3 and args.config == "2":
+        if cfg.d == 3 and cfg is gen.get_config(2):
             offs = gen.moore(3, 1)
             sizes = gen.stencil_block_sizes(offs, 64)
             icomm = iso.iso_neighborhood_create(cfg.dims, offs)
@@ -355,16 +458,14 @@ def main():
                 displs, ext = gen.packed_displacements(sizes, align)
                 isend = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
                 irecv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
-                for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("sx_fused", iso.ISO_ALG_SX_FUSED)):
+                for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
+                                  ("sx_fused", iso.ISO_ALG_SX_FUSED)):
                     wsb = iso.iso_workspace_bytes_v(icomm, iso.ISO_OP_ALLTOALL, alg, sizes)
                     iwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                     r = iso.iso_neighbor_alltoallv_init(isend, sizes, displs, ext, irecv, sizes, displs, ext,
                                                         iwork, icomm, alg)
-                    ms = time_steps([r], ksteps, 3) / ksteps
-                    inf = iso.iso_request_info(r)
-                    extras[f"alltoallv_stencil_base64_{tag}{name}"] = {
-                        "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
-                        "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+                    ms = self.time_steps([r], ksteps, 3) / ksteps
+                    extras[f"alltoallv_stencil_base64_{tag}{name}"] = rate([r], ms)
                     iso.iso_request_free(r)
                     del iwork
                 del isend, irecv
@@ -380,17 +481,13 @@ def main():
                 iwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                 r = iso.iso_neighbor_alltoallv_init_layout(psend, sizes, pd, 0, precv, sizes, pd, 0,
                                                            iso.ISO_LAYOUT_SLOT_MAJOR, iwork, icomm, alg)
-                ms = time_steps([r], ksteps, 3) / ksteps
-                inf = iso.iso_request_info(r)
-                extras[f"alltoallv_stencil_base64_slot_major_{name}"] = {
-                    "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
-                    "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+                ms = self.time_steps([r], ksteps, 3) / ksteps
+                extras[f"alltoallv_stencil_base64_slot_major_{name}"] = rate([r], ms)
                 iso.iso_request_free(r)
                 del iwork
             del psend, precv
         # the same collectives on slot-major buffers ([s][p][m], one plane per neighbour): every
         # block-move is a dense stream on both sides, whatever m is
-        sm_reqs = {}
         for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
                           ("sx_fused", iso.ISO_ALG_SX_FUSED)):
             rs, keepalive = [], []
@@ -399,26 +496,23 @@ def main():
                     sm_send = torch.empty((s, p, m), dtype=torch.uint8, device=dev).fill_(5)
                     init = iso.iso_neighbor_alltoall_init_layout
                 else:
-                    sm_send = bufs[op][0]
+                    sm_send = self.bufs[op][0]
                     init = iso.iso_neighbor_allgather_init_layout
                 sm_recv = torch.empty((s, p, m), dtype=torch.uint8, device=dev)
                 wsb = iso.iso_workspace_bytes(comm, op, alg, m)
                 sm_work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                 rs.append(init(sm_send, sm_recv, m, iso.ISO_LAYOUT_SLOT_MAJOR, sm_work, comm, alg))
                 keepalive += [sm_send, sm_recv, sm_work]
-            ms = time_steps(rs, ksteps, 3) / ksteps
-            mv = sum(iso.iso_request_info(r)["bytes_read"] * 2 for r in rs)
-            extras[f"slot_major_{name}"] = {
-                "ms_per_step": round(ms, 5), "delivered_GBs": round(delivered / ms / 1e6, 1),
-                "moved_GBs": round(mv / ms / 1e6, 1), "frac_of_peak": round(mv / ms / 1e6 / HBM_PEAK_GBS, 4),
-                "launches": sum(iso.iso_request_info(r)["launches"] for r in rs)}
+            ms = self.time_steps(rs, ksteps, 3) / ksteps
+            extras[f"slot_major_{name}"] = rate(rs, ms, hbm_label=not (name.startswith("sx") and
+                                                                       iso.ISO_OP_ALLGATHER in ops))
             for r in rs:
                 iso.iso_request_free(r)
             del rs, keepalive
             torch.cuda.empty_cache()
         # the all-to-all with every rank's row padded by 128 bytes (the irregular interface's extents):
         # where the row size s*m is a multiple of 4 KiB, all blocks of a round sit at one offset
-        # modulo 4 KiB and load a fraction of the memory channels; the padding spreads them
+        # modulo 4 KiB; the padding spreads them
         if iso.ISO_OP_ALLTOALL in ops and p * (s * m + 128) <= (2 << 30):
             ext = s * m + 128
             sizes, displs = [m] * s, [i * m for i in range(s)]
@@ -428,51 +522,50 @@ def main():
             pwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
             r = iso.iso_neighbor_alltoallv_init(psend, sizes, displs, ext, precv, sizes, displs, ext, pwork, comm,
                                                 iso.ISO_ALG_COMBINED)
-            ms = time_steps([r], ksteps, 3) / ksteps
-            inf = iso.iso_request_info(r)
-            extras["alltoall_rows_padded_128B_combined"] = {
-                "ms_per_step": round(ms, 5), "delivered_GBs": round(inf["delivered_bytes"] / ms / 1e6, 1),
-                "moved_GBs": round(2 * inf["bytes_read"] / ms / 1e6, 1),
-                "frac_of_peak": round(2 * inf["bytes_read"] / ms / 1e6 / HBM_PEAK_GBS, 4), "launches": inf["launches"]}
+            ms = self.time_steps([r], ksteps, 3) / ksteps
+            extras["alltoall_rows_padded_128B_combined"] = rate([r], ms)
             iso.iso_request_free(r)
             del psend, precv, pwork
             torch.cuda.empty_cache()
         # the same torus taken as a box (no dimension wraps, Section 7): blocks whose source lies
         # outside stay untouched; moved bytes are nominal (every entry counted at every rank)
-        if args.config == "2":
+        if cfg is gen.get_config(2):
             mcomm = iso.iso_neighborhood_create_mesh(cfg.dims, (0,) * cfg.d, cfg.offsets)
-            msend, mrecv = bufs[iso.ISO_OP_ALLTOALL]
+            msend, mrecv = self.bufs[iso.ISO_OP_ALLTOALL]
             for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("sx_fused", iso.ISO_ALG_SX_FUSED)):
                 wsb = iso.iso_workspace_bytes(mcomm, iso.ISO_OP_ALLTOALL, alg, m)
                 mwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                 r = iso.iso_neighbor_alltoall_init(msend, mrecv, m, mwork, mcomm, alg)
-                ms = time_steps([r], ksteps, 3) / ksteps
-                inf = iso.iso_request_info(r)
+                ms = self.time_steps([r], ksteps, 3) / ksteps
+                d = rate([r], ms)
                 extras[f"mesh_alltoall_{name}"] = {
-                    "ms_per_step": round(ms, 5), "delivered_GBs_nominal": round(inf["delivered_bytes"] / ms / 1e6, 1),
-                    "moved_GBs_nominal": round(2 * inf["bytes_read"] / ms / 1e6, 1), "launches": inf["launches"]}
+                    "ms_per_step": d["ms_per_step"], "delivered_GBs_nominal": d["delivered_GBs"],
+                    "moved_GBs_nominal": d["moved_GBs"], "frac_of_peak_nominal": d["frac_of_peak"],
+                    "launches": d["launches"]}
                 iso.iso_request_free(r)
                 del mwork
-        out["comparison"] = extras
         log(json.dumps(extras))
+        return extras
 
-    # ---- CPU-oracle leg (the only part of this file that touches oracle/) --------
-    # (1) sampled ranks of the timed configuration against the oracle's source-rank table,
-    # (2) the oracle's C twin timed on the host cores, (3) its whole result against the GPU's.
-    if not args.no_cpu_baseline:
+    # -- CPU-oracle leg (the only part of this file that touches oracle/) --------------
+    def cpu_leg(self, out, seconds):
+        """(1) sampled ranks of the timed configuration against the oracle's source-rank table,
+        (2) the oracle's C twin timed on the host cores, (3) its whole result against the GPU's."""
         from oracle import c_twin
         from oracle import iso_oracle as orc
+        iso, torch, gen, np, args, cfg = self.iso, self.torch, self.gen, self.np, self.args, self.cfg
+        p, s, m, dev, ops, slot = self.p, self.s, self.m, self.dev, self.ops, self.slot
         for op in ops:                                   # one more step of the timed requests, from scratch
-            timed[op][1].fill_(0xEE)
-        for r in reqs:
-            iso.iso_start(r, stream)
+            self.timed[op][1].fill_(0xEE)
+        for r in self.reqs:
+            iso.iso_start(r, self.stream)
         torch.cuda.synchronize()
         rng = np.random.default_rng(args.seed)
         sample = np.unique(rng.integers(0, p, size=min(p, 512)))
         src = torch.from_numpy(orc.source_ranks(cfg.dims, cfg.offsets, sample)).to(dev)
         slots = torch.arange(s, device=dev)[None, :]
         for op in ops:
-            recv = timed[op][1].permute(1, 0, 2) if slot else timed[op][1]      # view as [p][s][m]
+            recv = self.timed[op][1].permute(1, 0, 2) if slot else self.timed[op][1]      # view as [p][s][m]
             if op == iso.ISO_OP_ALLTOALL:
                 want = gen.block_bytes_torch(args.seed, src, slots, m, cfg.kind)
             else:
@@ -480,9 +573,7 @@ def main():
             if not bool(torch.equal(recv[torch.from_numpy(sample).to(dev)], want)):
                 log("bench.py: RESULT MISMATCH against the oracle; aborting")
                 sys.exit(3)
-        host = {}
-        for op in ops:
-            host[op] = bufs[op][0].cpu().numpy()
+        host = {op: self.bufs[op][0].cpu().numpy() for op in ops}
         outs = {op: np.empty((p, s, m), np.uint8) for op in ops}
         times, used = [], 1
         t_begin = time.perf_counter()
@@ -490,19 +581,22 @@ def main():
             t = time.perf_counter()
             for op in ops:
                 fn = c_twin.alltoall if op == iso.ISO_OP_ALLTOALL else c_twin.allgather
-                _, used = fn(cfg.dims, cfg.offsets, host[op], out=outs[op])
+                # threads: OpenMP's default the first time, then that same count explicitly (the
+                # one-thread runs of an earlier workload leave the runtime's setting at 1)
+                _, used = fn(cfg.dims, cfg.offsets, host[op], out=outs[op], threads=Bench.host_threads)
+                Bench.host_threads = Bench.host_threads or int(used)
             times.append(time.perf_counter() - t)
-            if (time.perf_counter() - t_begin > args.cpu_seconds and len(times) >= 3) or len(times) >= 5000:
+            if (time.perf_counter() - t_begin > seconds and len(times) >= 3) or len(times) >= 5000:
                 break
         for op in ops:                                   # the two sides agree on the whole buffer
-            got = timed[op][1].permute(1, 0, 2) if slot else timed[op][1]
+            got = self.timed[op][1].permute(1, 0, 2) if slot else self.timed[op][1]
             if not np.array_equal(outs[op], got.cpu().numpy()):
                 log("bench.py: GPU result differs from the C oracle")
                 sys.exit(3)
         out["verified_against_oracle"] = True
         t_med = median(times[1:]) if len(times) > 1 else times[0]
         out["cpu_baseline"] = {
-            "value": round(delivered / t_med / 1e9, 3), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "value": round(self.delivered / t_med / 1e9, 3), "unit": "GB/s", "cores": int(used), "kind": "oracle",
             "sample": f"whole workload ({'+'.join(cfg.ops)} of {cfg.name}, m={m}), {len(times)} repetitions, "
                       f"median; C twin of the oracle, OpenMP over ranks",
             "ms_per_step": round(t_med * 1e3, 3),
@@ -515,17 +609,76 @@ def main():
                 fn = c_twin.alltoall if op == iso.ISO_OP_ALLTOALL else c_twin.allgather
                 fn(cfg.dims, cfg.offsets, host[op], out=outs[op], threads=1)
             t1.append(time.perf_counter() - t)
-            if sum(t1) > args.cpu_seconds:
+            if sum(t1) > seconds / 2:
                 break
-        out["cpu_baseline"]["one_thread_GBs"] = round(delivered / median(t1) / 1e9, 3)
-        if delivered <= (1 << 29):
+        out["cpu_baseline"]["one_thread_GBs"] = round(self.delivered / median(t1) / 1e9, 3)
+        if self.delivered <= (1 << 29):
             t = time.perf_counter()
             for op in ops:
                 (orc.alltoall if op == iso.ISO_OP_ALLTOALL else orc.allgather)(cfg.dims, cfg.offsets, host[op])
-            out["cpu_baseline"]["numpy_oracle_GBs"] = round(delivered / (time.perf_counter() - t) / 1e9, 3)
+            out["cpu_baseline"]["numpy_oracle_GBs"] = round(self.delivered / (time.perf_counter() - t) / 1e9, 3)
 
-    for r in reqs:
-        iso.iso_request_free(r)
+    def close(self):
+        for r in self.reqs:
+            self.iso.iso_request_free(r)
+        self.reqs, self.bufs, self.timed, self.keep = [], {}, {}, []
+        self.torch.cuda.empty_cache()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        log("bench.py: this build runs on ONE GPU (all p virtual ranks live in one device's HBM); "
+            "--gpus must be 1.")
+        sys.exit(2)
+
+    import torch
+    import iso_inputs as gen
+    import paper_1606_07676_amd as iso
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    if args.small_sweep:
+        small_sweep()
+        return
+    iso.load_library()
+    torch.cuda.set_device(0)
+    t_start = time.perf_counter()
+
+    if args.config is not None:
+        todo = [(gen.get_config(args.config), args.m)]
+    else:          # headline first: the largest workload; then the others with blocks of 128 bytes and more
+        todo = [(gen.get_config(5), None), (gen.get_config(2), None), (gen.get_config(3), None),
+                (gen.get_config(4), None)]
+    results = []
+    for idx, (cfg, m_over) in enumerate(todo):
+        b = Bench(args, cfg, m_over or cfg.m)
+        res = b.run()
+        if args.no_extras and args.copy_reference and idx == 0:
+            res["copy_1GiB_GBs_read_plus_write"] = b.copy_reference_rate()
+        # the comparison algorithms: on the one workload asked for, else on config 2 (small and quick)
+        if not args.no_extras and b.plain and (args.config is not None or cfg is gen.get_config(2)) \
+                and args.algorithm == "combined" and not args.graph:
+            res["comparison"] = b.comparison()
+        if not args.no_cpu_baseline and b.plain:
+            b.cpu_leg(res, max(args.cpu_seconds, 10.0) if idx == 0 else args.cpu_seconds)
+        b.close()
+        results.append(res)
+        log(f"  [{time.perf_counter() - t_start:.1f} s since start]")
+
+    head = results[0]
+    out = {
+        "metric": METRIC, "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+    }
+    out.update({k: v for k, v in head.items() if k not in ("value", "unit", "ms_per_step")})
+    if len(results) > 1:
+        # the other workloads of the same run: same protocol, own roofline and CPU baseline
+        out["workloads"] = {r["config"]["profile_tag"]: {k: v for k, v in r.items() if k != "isolated_repetitions"}
+                            for r in results}
+        out["workloads"][head["config"]["profile_tag"]] = {"see": "top level of this line"}
     print(json.dumps(out), flush=True)
 
 
