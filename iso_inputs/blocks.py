@@ -48,14 +48,14 @@ def mix32(x):
 
 
 def _to_kind_np(words, kind):
-    if kind == "u32":
+    if kind in ("u32", "u8"):
         return words
     if kind == "f32":
         # top 24 bits k -> k * 2^-23 - 1, exact in binary32, in [-1, 1)
         k = (words >> np.uint32(8)).astype(np.float32)
         f = k * np.float32(2.0 ** -23) - np.float32(1.0)
         return f.view(np.uint32)
-    raise ValueError("kind must be 'u32' or 'f32'")
+    raise ValueError("kind must be 'u32', 'f32' or 'u8'")
 
 
 def block_words(seed, ranks, slots, n_words, kind="u32"):
@@ -69,17 +69,26 @@ def block_words(seed, ranks, slots, n_words, kind="u32"):
     return _to_kind_np(mix32(hs[..., None] ^ e), kind)
 
 
-def _as_bytes_np(words, m):
+def _as_bytes_np(words, m, kind="u32"):
+    if kind == "u8":                 # one draw per byte: its low 8 bits
+        return np.ascontiguousarray(words.astype(np.uint8))
     b = np.ascontiguousarray(words).view(np.uint8)
     return b[..., :m] if b.shape[-1] != m else b
 
 
+def _n_draws(m, kind):
+    """Mixer values one block of m bytes takes: one per 32-bit word, or one per byte
+    for 'u8' content (uniform random bytes, each byte its own draw)."""
+    return m if kind == "u8" else (m + 3) // 4
+
+
 def block_bytes(seed, ranks, slots, m, kind="u32"):
     """uint8 array broadcast(ranks, slots).shape + (m,): the first m bytes
-    (little-endian words) of each indexed block."""
+    (little-endian words) of each indexed block; kind 'u8': byte e is the low
+    byte of the mixer value for element e."""
     if kind == "f32" and m % 4:
         raise ValueError("f32 blocks need m % 4 == 0")
-    return _as_bytes_np(block_words(seed, ranks, slots, (m + 3) // 4, kind), m)
+    return _as_bytes_np(block_words(seed, ranks, slots, _n_draws(m, kind), kind), m, kind)
 
 
 def alltoall_send(seed, p, s, m, kind="u32", rank_lo=0, rank_hi=None):
@@ -90,15 +99,15 @@ def alltoall_send(seed, p, s, m, kind="u32", rank_lo=0, rank_hi=None):
         raise ValueError("f32 blocks need m % 4 == 0")
     ranks = np.arange(rank_lo, rank_hi, dtype=np.int64)[:, None]
     slots = np.arange(s, dtype=np.int64)[None, :]
-    return _as_bytes_np(block_words(seed, ranks, slots, (m + 3) // 4, kind), m)
+    return _as_bytes_np(block_words(seed, ranks, slots, _n_draws(m, kind), kind), m, kind)
 
 
 def allgather_send(seed, p, m, kind="u32", rank_lo=0, rank_hi=None):
     """Host send buffer rows of an allgather: uint8 (rows, m); one block per rank."""
     rank_hi = p if rank_hi is None else rank_hi
     ranks = np.arange(rank_lo, rank_hi, dtype=np.int64)
-    w = block_words(seed ^ ALLGATHER_TWEAK, ranks, np.zeros_like(ranks), (m + 3) // 4, kind)
-    return _as_bytes_np(w, m)
+    w = block_words(seed ^ ALLGATHER_TWEAK, ranks, np.zeros_like(ranks), _n_draws(m, kind), kind)
+    return _as_bytes_np(w, m, kind)
 
 
 # --------------------------------------------------------------------------
@@ -129,23 +138,25 @@ def block_words_torch(seed, ranks, slots, n_words, kind="u32"):
     hs = _mix32_t(hr + slots.to(torch.int32) * _s32(_K_SLOT) + _s32(_K_SLOT_ADD))
     e = torch.arange(n_words, dtype=torch.int32, device=dev) * _s32(_K_ELEM)
     w = _mix32_t(hs[..., None] ^ e)
-    if kind == "u32":
+    if kind in ("u32", "u8"):
         return w
     if kind == "f32":
         k = ((w >> 8) & 0xFFFFFF).to(torch.float32)
         return (k * (2.0 ** -23) - 1.0).view(torch.int32)
-    raise ValueError("kind must be 'u32' or 'f32'")
+    raise ValueError("kind must be 'u32', 'f32' or 'u8'")
 
 
-def _as_bytes_t(words, m):
+def _as_bytes_t(words, m, kind="u32"):
     import torch
+    if kind == "u8":
+        return (words & 0xFF).to(torch.uint8)
     b = words.contiguous().view(torch.uint8)
     return b[..., :m].contiguous() if b.shape[-1] != m else b
 
 
 def block_bytes_torch(seed, ranks, slots, m, kind="u32"):
     """torch twin of `block_bytes` (uint8 tensor on ranks.device)."""
-    return _as_bytes_t(block_words_torch(seed, ranks, slots, (m + 3) // 4, kind), m)
+    return _as_bytes_t(block_words_torch(seed, ranks, slots, _n_draws(m, kind), kind), m, kind)
 
 
 def alltoall_send_torch(seed, p, s, m, kind="u32", device="cpu", out=None,
@@ -155,10 +166,12 @@ def alltoall_send_torch(seed, p, s, m, kind="u32", device="cpu", out=None,
     if out is None:
         out = torch.empty((p, s, m), dtype=torch.uint8, device=device)
     slots = torch.arange(s, dtype=torch.int64, device=device)[None, :]
+    if kind == "u8":
+        rank_chunk = max(1, rank_chunk // 8)       # four bytes of intermediate per byte of output
     for lo in range(0, p, rank_chunk):
         hi = min(p, lo + rank_chunk)
         ranks = torch.arange(lo, hi, dtype=torch.int64, device=device)[:, None]
-        out[lo:hi] = _as_bytes_t(block_words_torch(seed, ranks, slots, (m + 3) // 4, kind), m)
+        out[lo:hi] = _as_bytes_t(block_words_torch(seed, ranks, slots, _n_draws(m, kind), kind), m, kind)
     return out
 
 
@@ -166,5 +179,5 @@ def allgather_send_torch(seed, p, m, kind="u32", device="cpu"):
     import torch
     ranks = torch.arange(p, dtype=torch.int64, device=device)
     w = block_words_torch(seed ^ ALLGATHER_TWEAK, ranks, torch.zeros_like(ranks),
-                          (m + 3) // 4, kind)
-    return _as_bytes_t(w, m)
+                          _n_draws(m, kind), kind)
+    return _as_bytes_t(w, m, kind)

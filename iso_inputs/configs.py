@@ -16,7 +16,7 @@ class Workload:
     dims: tuple            # torus dimension sizes p_0..p_{d-1}
     offsets: tuple         # s relative coordinate vectors, block order
     m: int                 # block size in bytes
-    kind: str              # "u32" | "f32" content
+    kind: str              # "u32" | "f32" | "u8" content
     ops: tuple             # subset of ("alltoall", "allgather")
     m_sweep: tuple = field(default=())
 
@@ -49,7 +49,7 @@ CONFIGS = (
     _mk("c4_torus64x64x64_moore1_m128", (64, 64, 64), moore(3, 1), 128, "u32",
         ("allgather", "alltoall"), sweep=(16, 64, 128)),
     _mk("c5_torus8x8x8x8x8_rand40_m4096", (8,) * 5,
-        random_distinct(5, -3, 3, 40, CONFIG5_NEIGHBOURHOOD_SEED), 4096, "u32",
+        random_distinct(5, -3, 3, 40, CONFIG5_NEIGHBOURHOOD_SEED), 4096, "u8",
         ("alltoall", "allgather")),
 )
 

@@ -60,17 +60,22 @@ struct alignas(16) DevEntry {
 // Workgroup -> tile mapping.  The hardware hands consecutive workgroup ids to
 // the 8 XCDs round-robin; each XCD has its own L2.  `run_log2` makes XCD x work
 // on runs of 2^run_log2 consecutive tiles (tile = 256 consecutive units), the 8
-// XCDs' runs interleaved, so that one L2 sees consecutive ranks (all of its
-// channels are used even when the rank stride s*m is a multiple of the channel
-// interleave) while the 8 XCDs still sweep the same region of memory together.
+// XCDs' runs interleaved, so that one L2 sees consecutive ranks while the 8 XCDs
+// still sweep the same region of memory together.  kEighths instead gives XCD x
+// the x-th contiguous eighth of all tiles: the host picks it for launches whose
+// blocks sit at rank strides that are multiples of 4 KiB and cover only part of a
+// 4 KiB page (see page_resonant), where it is 4 - 26 % faster.
 struct TileMap {
     uint32_t n_tiles;      // tiles that carry work
-    uint32_t run_log2;
+    uint32_t run_log2;     // kEighths: XCD x works on the x-th contiguous eighth of the tiles
+    uint32_t per_xcd;      // kEighths: tiles per XCD, ceil(n_tiles / 8)
 };
+constexpr uint32_t kEighths = 31;
 
 __device__ __forceinline__ bool tile_of_block(const TileMap &tm, uint32_t &tile) {
     const uint32_t bid = blockIdx.x, x = bid & 7u, y = bid >> 3;
-    tile = ((y >> tm.run_log2) << (tm.run_log2 + 3)) + (x << tm.run_log2) + (y & ((1u << tm.run_log2) - 1u));
+    if (tm.run_log2 == kEighths) tile = x * tm.per_xcd + y;
+    else tile = ((y >> tm.run_log2) << (tm.run_log2 + 3)) + (x << tm.run_log2) + (y & ((1u << tm.run_log2) - 1u));
     return tile < tm.n_tiles;
 }
 

@@ -7,7 +7,7 @@ import iso_inputs as gen
 
 
 def test_numpy_and_torch_generators_agree_bitwise():
-    for kind, m in (("u32", 32), ("u32", 7), ("f32", 64), ("u32", 4096)):
+    for kind, m in (("u32", 32), ("u32", 7), ("f32", 64), ("u32", 4096), ("u8", 48), ("u8", 5), ("u8", 4096)):
         a = gen.alltoall_send(3, 50, 5, m, kind)
         b = gen.alltoall_send_torch(3, 50, 5, m, kind, rank_chunk=16).numpy()
         assert a.dtype == np.uint8 and a.shape == (50, 5, m)
@@ -69,3 +69,15 @@ def test_bench_refuses_more_than_one_gpu():
                          stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True)
     assert out.returncode != 0 and out.stdout == ""
     assert "ONE GPU" in out.stderr
+
+
+def test_u8_blocks_are_one_draw_per_byte():
+    """Config 5's content: every byte its own mixer value (low 8 bits), so all 256 byte values
+    occur about equally often and bytes of one block are not the bytes of consecutive words."""
+    b = gen.alltoall_send(4, 8, 3, 4096, "u8")
+    assert b.dtype == np.uint8 and b.shape == (8, 3, 4096)
+    w = gen.block_words(4, np.arange(8)[:, None], np.arange(3)[None, :], 4096, "u8")
+    assert np.array_equal(b, (w & 0xFF).astype(np.uint8))
+    counts = np.bincount(b.reshape(-1), minlength=256)
+    assert counts.min() > 0.7 * b.size / 256 and counts.max() < 1.3 * b.size / 256
+    assert gen.get_config(5).kind == "u8"
