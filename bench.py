@@ -704,6 +704,10 @@ def main():
             comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
             ops = [iso.ISO_OP_ALLTOALL if o == "alltoall" else iso.ISO_OP_ALLGATHER for o in cfg.ops]
             need = max(need, Bench.arena_need(iso, comm, ops, cfg.p, cfg.s, m_over or cfg.m, args.layout == "slot", alg))
+        # at least 8 GiB: the driver backs an allocation of several GiB with large physical blocks even
+        # right after another process has freed tens of GB; a 2 GiB allocation made then can be scattered
+        # (config 3 alone, after a config 5 process: 0.450 ms per step instead of 0.383)
+        need = max(need, 8 << 30)
         Bench.arena = torch.empty(need + Bench.ALIGN, dtype=torch.uint8, device="cuda:0")
     for idx, (cfg, m_over) in enumerate(todo):
         b = Bench(args, cfg, m_over or cfg.m)

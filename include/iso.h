@@ -130,8 +130,12 @@ typedef struct {
 typedef struct {
     int32_t src_buf, src_slot;   /* enum iso_buffer, block index inside that buffer's row  */
     int32_t dst_buf, dst_slot;
-    int32_t shift;               /* SHIFT rounds: residue v in [0, p_j): the block comes
-                                    from the rank v steps back in `dim`; else 0            */
+    int32_t shift;               /* SHIFT rounds: the block comes from the rank `shift` steps
+                                    back in `dim`.  Periodic dimension: the residue v in
+                                    [0, p_j).  Non-periodic dimension of a mesh: the signed
+                                    coordinate as given (negative = the source lies forward,
+                                    magnitudes of p_j and more are legal and find no source
+                                    anywhere).  Other rounds: 0                            */
     int32_t neighbor;            /* index i of the offset whose route this move belongs to
                                     (allgather temporaries: -1); VECTOR rounds: source is
                                     R (-) C^neighbor                                        */
@@ -198,6 +202,10 @@ int iso_plan_free(iso_plan_t *plan);
  * that make two or more hops.  Allgather: trie nodes that are not themselves
  * neighbours.  The s-exchange algorithms need none. */
 int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t *bytes);
+/* The same for the message-combining schedule (ISO_ALG_COMBINED) of one operation:
+ * iso_workspace_bytes(comm, ISO_OP_ALLTOALL / ISO_OP_ALLGATHER, ISO_ALG_COMBINED, m, bytes). */
+int iso_alltoall_workspace_bytes(iso_comm_t comm, size_t m, size_t *bytes);
+int iso_allgather_workspace_bytes(iso_comm_t comm, size_t m, size_t *bytes);
 
 /* ---- persistent collectives (Section 2, init/start listing) ----------------
  * sendbuf:   device, read-only.  All-to-all: p*s blocks, [p][s][m], block (R,i)
@@ -224,6 +232,18 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m,
                                 void *workspace, size_t workspace_bytes,
                                 iso_comm_t comm, int algorithm, iso_request_t *req);
 
+/* The straightforward algorithm (first listing of Section 3: one exchange per
+ * neighbour) bound as a persistent request: the comparison baseline.
+ * mode: ISO_SX_LAUNCHES = one launch per neighbour, s launches (the listing taken
+ * literally; = ISO_ALG_SX_ROUNDS), ISO_SX_FUSED = all s exchanges in one launch
+ * (= ISO_ALG_SX_FUSED).  No workspace is needed.  Buffers, layout ([p][s][m]),
+ * results and errors as for iso_neighbor_alltoall_init / _allgather_init. */
+enum iso_sx_mode { ISO_SX_LAUNCHES = 0, ISO_SX_FUSED = 1 };
+int iso_neighbor_alltoall_sx_init(const void *sendbuf, void *recvbuf, size_t m, int mode,
+                                  iso_comm_t comm, iso_request_t *req);
+int iso_neighbor_allgather_sx_init(const void *sendbuf, void *recvbuf, size_t m, int mode,
+                                   iso_comm_t comm, iso_request_t *req);
+
 /* The same two collectives with the layout of the caller's buffers chosen by
  * `layout` (enum iso_layout).  ISO_LAYOUT_RANK_MAJOR is exactly the calls above.
  * ISO_LAYOUT_SLOT_MAJOR: sendbuf (all-to-all) and recvbuf are [s][p][m]: block
@@ -249,9 +269,15 @@ int iso_neighbor_allgather_init_layout(const void *sendbuf, void *recvbuf, size_
  *   sendbuf: device, rank R's row starts at sendbuf + R*send_extent (read-only);
  *   recvbuf: device, likewise; bytes of a row outside the s blocks are not touched.
  * Blocks of size 0 are legal and move nothing.  Each block is moved in units of
- * the widest power of two (<= 16 bytes) dividing its size, its addresses and the
- * extents, so a 1-byte block next to a 16 KiB block does not narrow the latter.
- * Workspace: iso_workspace_bytes_v().  Other rules as for the regular calls. */
+ * its own width: 16 bytes for blocks of 16 bytes and more, below that the largest
+ * power of two that is at most the block size (the last unit of a block overlaps
+ * its predecessor when the width does not divide the size), so a 1-byte block
+ * next to a 16 KiB block does not narrow the latter.  Addresses, displacements
+ * and extents need no alignment; rows whose blocks start on 128-byte boundaries
+ * are written fastest.
+ * Workspace: iso_workspace_bytes_v() (sizes: host, s values; for ISO_OP_ALLGATHER
+ * they must all be equal, as in the init call, else ISO_ERR_ARG).  Other rules as
+ * for the regular calls. */
 int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *sizes, size_t *bytes);
 int iso_neighbor_alltoallv_init(const void *sendbuf, const size_t *send_sizes, const size_t *send_displs,
                                 size_t send_extent, void *recvbuf, const size_t *recv_sizes,
@@ -309,12 +335,16 @@ int iso_start_range(iso_request_t req, int first, int count, void *hip_stream);
  * cost is dominated by the per-round start-up.  enable == 0: back to individual
  * launches.  iso_start_range is unaffected.  The result is the same either way. */
 int iso_request_set_graph(iso_request_t req, int enable);
-/* Blocks the host until the most recent iso_start of this request completed
- * (Section 7's proposed completion call). */
+/* Blocks the host until the most recent iso_start / iso_start_range of this
+ * request completed (Section 7's proposed completion call).  Only the stream of
+ * that most recent call is waited for: a caller that starts ranges of one request
+ * on several streams synchronises the earlier streams itself. */
 int iso_wait(iso_request_t req);
 int iso_request_info(iso_request_t req, iso_request_info_t *info);
 /* Returns the plan the request executes (owned by the request; do not free). */
 int iso_request_plan(iso_request_t req, iso_plan_t *plan);
+/* Waits for the request's most recent start (as iso_wait does), then frees the
+ * handle, its graph and its device table, and sets *req = NULL. */
 int iso_request_free(iso_request_t *req);
 
 /* ---- for callers that cannot allocate device memory -------------------------

@@ -18,6 +18,7 @@ ISO_OP_ALLTOALL, ISO_OP_ALLGATHER = 0, 1
 ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP = 0, 1, 2, 3, 4
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
 ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR = 0, 1
+ISO_SX_LAUNCHES, ISO_SX_FUSED = 0, 1
 ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR = 0, 1, 2
 
 
@@ -91,6 +92,10 @@ _PROTOTYPES = {
     "iso_plan_entries": ([_VP, _I, ctypes.POINTER(iso_plan_entry_t), _I], _I),
     "iso_plan_free": ([ctypes.POINTER(_VP)], _I),
     "iso_workspace_bytes": ([_VP, _I, _I, _SZ, ctypes.POINTER(_SZ)], _I),
+    "iso_alltoall_workspace_bytes": ([_VP, _SZ, ctypes.POINTER(_SZ)], _I),
+    "iso_allgather_workspace_bytes": ([_VP, _SZ, ctypes.POINTER(_SZ)], _I),
+    "iso_neighbor_alltoall_sx_init": ([_VP, _VP, _SZ, _I, _VP, ctypes.POINTER(_VP)], _I),
+    "iso_neighbor_allgather_sx_init": ([_VP, _VP, _SZ, _I, _VP, ctypes.POINTER(_VP)], _I),
     "iso_neighbor_alltoall_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_neighbor_allgather_init": ([_VP, _VP, _SZ, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
     "iso_neighbor_alltoall_init_layout": ([_VP, _VP, _SZ, _I, _VP, _SZ, _VP, _I, ctypes.POINTER(_VP)], _I),
@@ -297,6 +302,35 @@ def iso_workspace_bytes(comm, op, algorithm, m):
     _check(load_library().iso_workspace_bytes(comm.handle, op, algorithm, m, ctypes.byref(out)),
            "iso_workspace_bytes")
     return out.value
+
+
+def iso_alltoall_workspace_bytes(comm, m):
+    out = ctypes.c_size_t()
+    _check(load_library().iso_alltoall_workspace_bytes(comm.handle, m, ctypes.byref(out)),
+           "iso_alltoall_workspace_bytes")
+    return out.value
+
+
+def iso_allgather_workspace_bytes(comm, m):
+    out = ctypes.c_size_t()
+    _check(load_library().iso_allgather_workspace_bytes(comm.handle, m, ctypes.byref(out)),
+           "iso_allgather_workspace_bytes")
+    return out.value
+
+
+def _sx_init(name, sendbuf, recvbuf, m, mode, comm):
+    h = ctypes.c_void_p()
+    st = getattr(load_library(), name)(_ptr(sendbuf), _ptr(recvbuf), m, mode, comm.handle, ctypes.byref(h))
+    _check(st, name)
+    return Request(h.value, (sendbuf, recvbuf))
+
+
+def iso_neighbor_alltoall_sx_init(sendbuf, recvbuf, m, mode, comm):
+    return _sx_init("iso_neighbor_alltoall_sx_init", sendbuf, recvbuf, m, mode, comm)
+
+
+def iso_neighbor_allgather_sx_init(sendbuf, recvbuf, m, mode, comm):
+    return _sx_init("iso_neighbor_allgather_sx_init", sendbuf, recvbuf, m, mode, comm)
 
 
 def _init(name, sendbuf, recvbuf, m, workspace, workspace_bytes, comm, algorithm):

@@ -361,6 +361,14 @@ int iso_workspace_bytes(iso_comm_t comm, int op, int algorithm, size_t m, size_t
     });
 }
 
+int iso_alltoall_workspace_bytes(iso_comm_t comm, size_t m, size_t *bytes) {
+    return iso_workspace_bytes(comm, ISO_OP_ALLTOALL, ISO_ALG_COMBINED, m, bytes);
+}
+
+int iso_allgather_workspace_bytes(iso_comm_t comm, size_t m, size_t *bytes) {
+    return iso_workspace_bytes(comm, ISO_OP_ALLGATHER, ISO_ALG_COMBINED, m, bytes);
+}
+
 int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *sizes, size_t *bytes) {
     return guarded([&]() -> int {
         if (!comm || !bytes || (comm->c.s > 0 && !sizes)) return ISO_ERR_ARG;
@@ -369,6 +377,9 @@ int iso_workspace_bytes_v(iso_comm_t comm, int op, int algorithm, const size_t *
         if (st != ISO_SUCCESS) return st;
         iso::Layout lay;
         lay.size.assign(sizes, sizes + comm->c.s);
+        if (op == ISO_OP_ALLGATHER)                       // every process sends one size
+            for (int i = 1; i < comm->c.s; ++i)
+                if (sizes[i] != sizes[0]) return ISO_ERR_ARG;
         if (sizes_too_large(comm->c, lay.size)) return ISO_ERR_TOO_LARGE;
         *bytes = (size_t)iso::work_layout(pl, lay).bytes;
         return ISO_SUCCESS;
@@ -390,6 +401,26 @@ int iso_neighbor_allgather_init(const void *sendbuf, void *recvbuf, size_t m, vo
     return guarded([&]() -> int {
         return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, ISO_LAYOUT_RANK_MAJOR, workspace,
                             workspace_bytes, comm, algorithm, req);
+    });
+}
+
+int iso_neighbor_alltoall_sx_init(const void *sendbuf, void *recvbuf, size_t m, int mode, iso_comm_t comm,
+                                  iso_request_t *req) {
+    return guarded([&]() -> int {
+        if (req) *req = nullptr;
+        if (mode != ISO_SX_LAUNCHES && mode != ISO_SX_FUSED) return ISO_ERR_ARG;
+        return init_regular(ISO_OP_ALLTOALL, sendbuf, recvbuf, m, ISO_LAYOUT_RANK_MAJOR, nullptr, 0, comm,
+                            mode == ISO_SX_FUSED ? ISO_ALG_SX_FUSED : ISO_ALG_SX_ROUNDS, req);
+    });
+}
+
+int iso_neighbor_allgather_sx_init(const void *sendbuf, void *recvbuf, size_t m, int mode, iso_comm_t comm,
+                                   iso_request_t *req) {
+    return guarded([&]() -> int {
+        if (req) *req = nullptr;
+        if (mode != ISO_SX_LAUNCHES && mode != ISO_SX_FUSED) return ISO_ERR_ARG;
+        return init_regular(ISO_OP_ALLGATHER, sendbuf, recvbuf, m, ISO_LAYOUT_RANK_MAJOR, nullptr, 0, comm,
+                            mode == ISO_SX_FUSED ? ISO_ALG_SX_FUSED : ISO_ALG_SX_ROUNDS, req);
     });
 }
 
@@ -588,6 +619,15 @@ int iso_request_free(iso_request_t *req) {
     if (!req) return ISO_ERR_ARG;
     int st = ISO_SUCCESS;
     if (*req) {
+        // the last collective may still be running: its kernels read the device table
+        if ((*req)->started && !(*req)->b.launches.empty()) {
+            hipError_t e = hipStreamSynchronize((*req)->last_stream);
+            if (e != hipSuccess) {
+                g_last_hip_error = (int)e;
+                (void)hipGetLastError();
+                st = ISO_ERR_HIP;
+            }
+        }
         if ((*req)->graph_exec) (void)hipGraphExecDestroy((*req)->graph_exec);
         if ((*req)->graph) (void)hipGraphDestroy((*req)->graph);
         if ((*req)->b.dev_table) {

@@ -40,6 +40,7 @@ struct Launch {
     bool mesh;
     bool stream_loads;     // every source block is read exactly once in this launch: non-temporal loads
     bool tail;             // regular kernels: the last unit of a block overlaps the one before it
+    bool uniform_waves;    // shift kernel, 16-byte units, blocks a multiple of 64 units: one block per wavefront
 
     ShiftArgs shift;
     VectorArgs vec;
@@ -217,6 +218,11 @@ void enqueue_regular(const Launch &l, hipStream_t stream) {
         return;
     }
     if constexpr (sizeof(V) == 16) {
+        if (l.uniform_waves) {
+            if (l.stream_loads) hipLaunchKernelGGL((shift_round_uniform_kernel<true>), grid, block, 0, stream, l.shift);
+            else hipLaunchKernelGGL((shift_round_uniform_kernel<false>), grid, block, 0, stream, l.shift);
+            return;
+        }
         if (l.stream_loads) {
             hipLaunchKernelGGL((shift_round_kernel<V, LDS, true, TAIL>), grid, block, 0, stream, l.shift);
             return;
@@ -452,6 +458,10 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 k = (uint32_t)std::min<uint64_t>(kMaxUnits / per_entry, ents.size() - done);
                 total = per_entry * k;
                 l.kernel = r.kind == ISO_ROUND_VECTOR ? kVectorKernel : c.mesh ? kMeshShiftKernel : kShiftKernel;
+                // one block per wavefront: blocks that are a multiple of 1 KiB; on rank-major buffers only up
+                // to 2 KiB (measured: no gain from 4 KiB on)
+                l.uniform_waves = l.kernel == kShiftKernel && min_log2 == 4 && !l.tail && chunks % 64 == 0 &&
+                                  (lay.slot_major || chunks <= 128);
                 const FastDiv dch = make_fastdiv((uint32_t)chunks), dk = make_fastdiv(k);
                 const FastDiv dp = make_fastdiv((uint32_t)p);
                 if (l.kernel == kVectorKernel) {
@@ -477,11 +487,57 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     ma.d_p = dp;
                     ma.entry_major = lay.slot_major;
                     ma.last_offset = size0 - width;
+                    ma.d_inner = make_fastdiv(ma.inner);
+                    ma.d_pj = make_fastdiv(ma.pj);
                     for (int j = 0; j < c.d; ++j) {
                         if (c.periodic[(size_t)j]) ma.periodic_mask |= 1u << j;
                         ma.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
                         ma.inner_of[j] = (uint32_t)c.inner[j];
                     }
+                    // Coordinates at which every entry of the launch finds its source: r_l - c_l in [0, p_l)
+                    // for all masked dimensions l of all entries.  A tile is interior if its ranks share
+                    // all coordinates but the last and lie inside these bounds (conservative: a tile that
+                    // crosses into the next row of the last dimension counts as not interior).
+                    std::vector<int64_t> in_lo((size_t)c.d, 0), in_hi((size_t)c.d, 0);
+                    bool has_interior = true;
+                    for (int j = 0; j < c.d; ++j) {
+                        int64_t lo = 0, hi = c.dims[j];
+                        for (uint32_t q = 0; q < k; ++q) {
+                            const DevEntry &de = ents[done + q].de;
+                            if (!(((de.meta >> 8) >> j) & 1u)) continue;
+                            const int64_t cl = c.c((int)de.ref, j);
+                            lo = std::max<int64_t>(lo, cl);
+                            hi = std::min<int64_t>(hi, (int64_t)c.dims[j] + cl);
+                        }
+                        if (lo >= hi) has_interior = false;
+                        in_lo[(size_t)j] = lo;
+                        in_hi[(size_t)j] = hi;
+                    }
+                    const uint64_t n_tiles = (total + kThreads - 1) / kThreads;
+                    std::vector<uint32_t> bits((size_t)((n_tiles + 31) / 32), 0u);
+                    for (uint64_t tl = 0; has_interior && tl < n_tiles; ++tl) {
+                        const uint64_t u0 = tl * kThreads, u1 = std::min<uint64_t>(u0 + kThreads, total) - 1;
+                        const uint64_t t0 = u0 / chunks, t1 = u1 / chunks;
+                        uint64_t R0, R1;
+                        if (lay.slot_major) {              // (entry, rank, chunk): one entry per interior tile
+                            if (t0 / p != t1 / p) continue;
+                            R0 = t0 % p;
+                            R1 = t1 % p;
+                        } else {                           // (rank, entry, chunk)
+                            R0 = t0 / k;
+                            R1 = t1 / k;
+                        }
+                        uint64_t rem = R0;
+                        bool inside = true;
+                        for (int j = c.d - 1; j >= 0 && inside; --j) {
+                            const int64_t r = (int64_t)(rem % (uint64_t)c.dims[j]);
+                            rem /= (uint64_t)c.dims[j];
+                            const int64_t last = j == c.d - 1 ? r + (int64_t)(R1 - R0) : r;
+                            inside = r >= in_lo[(size_t)j] && last < in_hi[(size_t)j];
+                        }
+                        if (inside) bits[(size_t)(tl >> 5)] |= 1u << (tl & 31);
+                    }
+                    prefixes.insert(prefixes.end(), bits.begin(), bits.end());
                 } else {
                     const bool shift = r.kind == ISO_ROUND_SHIFT;
                     l.shift.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
@@ -496,41 +552,68 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 }
                 for (uint32_t q = 0; q < k; ++q) table.push_back(ents[done + q].de);
             } else {
-                // irregular blocks, or a mesh: as many entries as fit the 32-bit unit index
+                // irregular blocks, or a mesh: as many entries as fit the 32-bit unit index (each of the
+                // at most kBlockSegments segments is padded to whole tiles)
                 l.kernel = kBlockKernel;
                 l.mesh = c.mesh;
                 l.block.shift_dim = r.kind == ISO_ROUND_SHIFT ? r.dim : -1;
                 for (int j = 0; j < c.d; ++j)
                     if (c.periodic[(size_t)j]) l.block.periodic_mask |= 1u << j;
-                // per launch: k + 1 prefix values, then k multipliers of the divisions by the entries'
-                // unit counts (entry-major order only; the two shifts go into the entry's meta word)
                 const bool entry_major = lay.slot_major;
                 const uint64_t scale = entry_major ? p : 1;    // prefix counts all ranks' units, or one row's
                 uint64_t row_units = 0;
-                prefixes.push_back(0);
                 while (done + k < ents.size()) {
                     const uint64_t next = row_units + ents[done + k].de.units;
-                    if (next * p > kMaxUnits) break;
+                    if (next * p + kBlockSegments * kThreads > kMaxUnits) break;
                     row_units = next;
-                    DevEntry de = ents[done + k].de;
-                    const FastDiv by_units = make_fastdiv(de.units);
-                    de.meta |= (by_units.sh1 << 24) | (by_units.sh2 << 25);
-                    table.push_back(de);
-                    prefixes.push_back((uint32_t)(row_units * scale));
                     ++k;
                 }
                 if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
-                for (uint32_t q = 0; q < k; ++q) prefixes.push_back(make_fastdiv(ents[done + q].de.units).mul);
-                total = row_units * p;
+                // one segment per unit width, narrowest first; inside a segment the entries keep their order.
+                // Per segment: k_c + 1 prefix values, then k_c multipliers of the divisions by the entries'
+                // unit counts (entry-major order only; the two shifts go into the entry's meta word)
                 BlockArgs &b = l.block;
+                std::vector<size_t> order;                     // the launch's entries, segment by segment
+                uint32_t tiles = 0, nseg = 0;
+                for (int l2 = 0; l2 <= 4; ++l2) {
+                    std::vector<size_t> members;
+                    for (uint32_t q = 0; q < k; ++q)
+                        if ((ents[done + q].de.meta & 0xFFu) == (uint32_t)l2) members.push_back(done + q);
+                    if (members.empty()) continue;
+                    BlockSegment &sg = b.seg[nseg++];
+                    sg.first_tile = tiles;
+                    sg.first_entry = (uint32_t)order.size();
+                    sg.first_prefix = (uint32_t)(prefixes.size() - pd.first_prefix);
+                    sg.k = (uint32_t)members.size();
+                    sg.width_log2 = (uint32_t)l2;
+                    uint64_t seg_row = 0;
+                    prefixes.push_back(0);
+                    sg.equal_units = ents[members[0]].de.units;
+                    for (size_t mi : members) {
+                        DevEntry de = ents[mi].de;
+                        if (de.units != sg.equal_units) sg.equal_units = 0;
+                        seg_row += de.units;
+                        prefixes.push_back((uint32_t)(seg_row * scale));
+                        order.push_back(mi);
+                    }
+                    for (size_t mi : members) prefixes.push_back(make_fastdiv(ents[mi].de.units).mul);
+                    sg.total = (uint32_t)(seg_row * p);
+                    sg.d_row = make_fastdiv((uint32_t)seg_row);
+                    sg.d_units = make_fastdiv(sg.equal_units ? sg.equal_units : 1u);
+                    sg.d_plane = make_fastdiv(sg.equal_units ? (uint32_t)(p * sg.equal_units) : 1u);
+                    tiles += (uint32_t)(((uint64_t)sg.total + kThreads - 1) / kThreads);
+                }
+                for (size_t mi : order) {
+                    DevEntry de = ents[mi].de;
+                    const FastDiv by_units = make_fastdiv(de.units);
+                    de.meta |= (by_units.sh1 << 24) | (by_units.sh2 << 25);
+                    table.push_back(de);
+                }
+                total = (uint64_t)tiles * kThreads;
+                b.n_segments = nseg;
+                b.n_prefix = (uint32_t)(prefixes.size() - pd.first_prefix);
                 b.entry_major = entry_major;
-                b.equal_units = ents[done].de.units;
-                for (uint32_t q = 1; q < k; ++q)
-                    if (ents[done + q].de.units != b.equal_units) b.equal_units = 0;
-                b.d_units = make_fastdiv(b.equal_units ? b.equal_units : 1u);
-                b.d_plane = make_fastdiv(b.equal_units ? (uint32_t)(p * b.equal_units) : 1u);
                 b.vector_round = r.kind == ISO_ROUND_VECTOR;
-                b.d_row = make_fastdiv((uint32_t)row_units);
                 const bool shift = r.kind == ISO_ROUND_SHIFT;
                 b.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
                 b.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
@@ -546,7 +629,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             // s-exchange kernels are faster with cacheable loads)
             l.stream_loads = op == ISO_OP_ALLTOALL && r.kind != ISO_ROUND_VECTOR &&
                              (l.kernel == kShiftKernel || l.kernel == kMeshShiftKernel ||
-                              (l.kernel == kBlockKernel && l.block.equal_units));
+                              (l.kernel == kBlockKernel && l.block.n_segments == 1 && l.block.seg[0].equal_units));
             std::vector<Side> src_sides, dst_sides;
             for (uint32_t q = 0; q < k; ++q) {
                 const HostEntry &he = ents[done + q];
@@ -588,6 +671,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
         } else if (pd.l.kernel == kMeshShiftKernel) {
             pd.l.mesh_shift.entries = dev_entries + pd.first_entry;
             pd.l.mesh_shift.offsets = dev_offsets;
+            pd.l.mesh_shift.interior = dev_prefix + pd.first_prefix;
         } else if (pd.l.kernel == kBlockKernel) {
             pd.l.block.entries = dev_entries + pd.first_entry;
             pd.l.block.prefix = dev_prefix + pd.first_prefix;

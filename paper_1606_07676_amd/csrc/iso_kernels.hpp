@@ -131,7 +131,11 @@ __device__ __forceinline__ void move_unit(uint64_t dst, uint64_t src, uint64_t o
     V v;
     if constexpr (NTL) v = __builtin_nontemporal_load(sp);
     else v = *sp;
-    __builtin_nontemporal_store(v, (dst_ptr)(dst + off));
+    // Streaming stores for 16-byte units only.  Narrower units belong to blocks of a few bytes, of
+    // which several wavefronts write different bytes of one cache line: plain stores let the L2
+    // merge them before the line goes to memory.
+    if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(v, (dst_ptr)(dst + off));
+    else *(dst_ptr)(dst + off) = v;
 }
 
 template <typename V>
@@ -223,6 +227,20 @@ __device__ __forceinline__ uint32_t vector_source_rank(uint32_t R, const uint32_
     return srcR;
 }
 
+// Makes the compiler fetch these launch constants here, in one batch of scalar loads, instead of
+// each in front of its first use behind some branch (every such fetch is a wait of its own).
+__device__ __forceinline__ void fetch_now(const FastDiv &f) { asm volatile("" ::"s"(f.mul), "s"(f.sh1), "s"(f.sh2), "s"(f.div)); }
+
+__device__ __forceinline__ void fetch_now(const ShiftArgs &a) {
+    asm volatile("" ::"s"(a.entries), "s"(a.map.n_tiles), "s"(a.map.run_log2), "s"(a.map.per_xcd), "s"(a.total),
+                 "s"(a.k), "s"(a.inner), "s"(a.pj), "s"(a.entry_major));
+    fetch_now(a.d_chunks);
+    fetch_now(a.d_k);
+    fetch_now(a.d_inner);
+    fetch_now(a.d_pj);
+    fetch_now(a.d_p);
+}
+
 template <typename V, bool LDS, bool NTL, bool TAIL>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
@@ -246,6 +264,36 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
                       unit_offset_if<V, TAIL>(ch, a.last_offset));
 }
 
+// The same round for blocks that are a multiple of 1 KiB (64 units of 16 bytes): the 64 units of a
+// wavefront then belong to one block, so rank, entry and source rank are the same for all its lanes
+// and are computed once, in scalar registers, the entry fetched with scalar loads.  No staging of the
+// table through LDS, no barrier, no vector-memory access in front of the one load that matters: what
+// bounds these kernels is how long a wavefront holds its slot before that load is under way.
+template <bool NTL>
+__global__ __launch_bounds__(kThreads) void shift_round_uniform_kernel(const ShiftArgs a) {
+    fetch_now(a);
+    uint32_t tile;
+    if (!tile_of_block(a.map, tile)) return;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t u0 = tile * (uint32_t)kThreads + wave * 64u;      // first unit of this wavefront
+    if (u0 >= a.total) return;                                       // total is a multiple of 64
+    uint32_t t, ch0, R, e;
+    fast_divmod(u0, a.d_chunks, t, ch0);
+    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
+    else fast_divmod(t, a.d_k, R, e);
+    const uint32_t q = fast_div(R, a.d_inner);
+    const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
+    // the table is never written while a collective runs: read it as constant memory, through the scalar cache
+    typedef const DevEntry __attribute__((address_space(4))) *const_entry_ptr;
+    const const_entry_ptr en = (const_entry_ptr)(uintptr_t)(a.entries + e);
+    const uint32_t shift = en->shift;
+    uint32_t srcR = R - shift * a.inner;
+    if (rj < shift) srcR += a.pj * a.inner;
+    const uint64_t src = block_address(en->src, srcR, en->src_stride);
+    const uint64_t dst = block_address(en->dst, R, en->dst_stride);
+    move_unit<vec16_t, NTL>(dst, src, (uint64_t)(ch0 + (threadIdx.x & 63u)) * sizeof(vec16_t));
+}
+
 template <typename V, bool LDS, bool TAIL>
 __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
@@ -267,34 +315,58 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
 // Irregular blocks (the v/w interfaces of Section 2): every entry has its own
 // block size and its own unit width (16 bytes for blocks of at least 16 bytes,
 // narrower below, e.g. a 1-byte corner block next to a 16 KiB face block).
-// A rank's units are the concatenation of its entries' units; `prefix[e]` is
-// the first unit of entry e.  The flat index is split into (rank, unit in row),
-// the entry is found by binary search in the prefix array.  On slot-major
-// buffers (one plane of p blocks per neighbour) the order is (entry, rank, unit)
-// instead: prefix[e] then counts the units of all ranks in the entries before e,
-// and the position inside the plane is divided by the entry's own unit count.
+// A launch is cut into segments, one per unit width that occurs, narrowest first,
+// each padded to whole tiles, so that a workgroup (hence every wavefront) moves
+// units of ONE width and the choice of the access width is a uniform branch.
+// (What tiny blocks cost is not in the kernel: a block of a few bytes in every
+// rank's row costs a memory row activation per block on each side, whatever
+// moves it.  On the stencil-shaped all-to-all of Section 4, 4096 / 64 / 1 byte
+// blocks, the 6 % of bytes in the small blocks take a quarter of the time, and a
+// fifth of the fused s-exchange's.)  Inside a segment a rank's
+// units are the concatenation of the units of the segment's entries; `prefix[e]`
+// is the first unit of entry e.  The flat index is split into (rank, unit in
+// row), the entry is found by division when the segment's blocks are equal,
+// else by binary search in the prefix array.  On slot-major buffers (one plane
+// of p blocks per neighbour) the order is (entry, rank, unit) instead: prefix[e]
+// then counts the units of all ranks in the entries before e, and the position
+// inside the plane is divided by the entry's own unit count.
 //
 // MESH (Section 7, non-periodic dimensions): coordinates of non-periodic
 // dimensions are signed and nothing wraps there.  A move happens at rank R only
 // if R - C^ref stays inside the mesh in every dimension of the entry's mask
 // (the non-periodic dimensions routed up to and including this round in which
 // C^ref is non-zero); otherwise the destination keeps its content.
+struct BlockSegment {
+    uint32_t first_tile;       // tiles of the segments are consecutive
+    uint32_t first_entry;      // of this segment in the launch's entry table
+    uint32_t first_prefix;     // of this segment's [k + 1] prefix values and [k] multipliers in the prefix array
+    uint32_t k;                // entries
+    uint32_t total;            // units of this segment = p * units of a row
+    uint32_t width_log2;       // log2 of the unit width in bytes
+    uint32_t equal_units;      // != 0: every entry of the segment has this many units (no search)
+    uint32_t reserved;
+    FastDiv d_row, d_units, d_plane;   // units of a row; equal_units; p * equal_units
+};
+constexpr uint32_t kBlockSegments = 5;    // unit widths 16, 8, 4, 2, 1
+
 struct BlockArgs {
     const DevEntry *entries;
-    const uint32_t *prefix;    // [k + 1] first unit of every entry, then [k] multipliers (entry-major order)
+    const uint32_t *prefix;
     const uint32_t *offsets;   // [s][d] effective coordinates (residues; signed where non-periodic)
     TileMap map;
-    uint32_t total;            // p * row_units
-    uint32_t k;
+    uint32_t total;            // tiles * 256
+    uint32_t k;                // entries of all segments
+    uint32_t n_prefix;         // words of all segments' prefix arrays
+    uint32_t n_segments;
     uint32_t vector_round;     // 0: shift along one dimension, 1: full offset vector
     uint32_t inner, pj;        // shift rounds
     int32_t shift_dim;         // shift rounds: the dimension (-1: same-rank copy)
     uint32_t periodic_mask;    // bit j set: dimension j wraps
     int32_t d;
-    uint32_t equal_units;      // != 0: every entry of the launch has this many units (no search)
     uint32_t entry_major;      // slot-major buffers: units ordered (entry, rank, unit) and prefix[e] counts
                                // the units of all ranks before entry e; else (rank, entry, unit)
-    FastDiv d_row, d_inner, d_pj, d_units, d_plane;   // d_plane: p * equal_units
+    FastDiv d_inner, d_pj;
+    BlockSegment seg[kBlockSegments];
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
@@ -382,27 +454,38 @@ __device__ __forceinline__ bool mesh_source_rank(const Args &a, const DevEntry &
 template <bool LDS, bool MESH, bool NTL>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
-    __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
+    __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + kBlockSegments : 1];
     const uint32_t *prefix = a.prefix;
     if constexpr (LDS) {
-        for (uint32_t q = threadIdx.x; q <= 2 * a.k; q += kThreads) lds_prefix[q] = a.prefix[q];
+        for (uint32_t q = threadIdx.x; q < a.n_prefix; q += kThreads) lds_prefix[q] = a.prefix[q];
         prefix = lds_prefix;
     }
     const EntryTable<LDS> table(a.entries, a.k, lds);     // synchronises the workgroup when LDS
     uint32_t tile;
     if (!tile_of_block(a.map, tile)) return;
-    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
-    if (u >= a.total) return;
-    // flat index -> rank R, entry lo, unit ch of that entry's block
+    // The segment of this tile (uniform in the workgroup), chosen as a pointer into the argument
+    // struct with compile-time indices: the struct is then still read straight from the kernel
+    // argument segment with scalar loads.  (Everything below exists once per kernel on purpose: the
+    // compiler gives up that direct reading, and has every lane copy the 800-byte struct to private
+    // memory first, once the struct is read at more than a few hundred places.)
+    const BlockSegment *sp = &a.seg[0];
+#pragma unroll
+    for (uint32_t q = 1; q < kBlockSegments; ++q)
+        if (q < a.n_segments && tile >= a.seg[q].first_tile) sp = &a.seg[q];
+    const BlockSegment &sg = *sp;
+    const uint32_t u = (tile - sg.first_tile) * (uint32_t)kThreads + threadIdx.x;
+    if (u >= sg.total) return;
+    prefix += sg.first_prefix;
+    // flat index -> rank R, entry lo of the segment, unit ch of that entry's block
     uint32_t R = 0, lo = 0, ch = 0, w = u;
-    if (!a.entry_major) fast_divmod(u, a.d_row, R, w);    // w: unit inside the rank's row
+    if (!a.entry_major) fast_divmod(u, sg.d_row, R, w);   // w: unit inside the rank's row
     // entry-major: w counts through the entries one after another, each with the units of all p ranks
-    if (a.k == 1) {
+    if (sg.k == 1) {
         ch = w;
-    } else if (a.equal_units) {                            // equal blocks: plain division, no search
-        fast_divmod(w, a.entry_major ? a.d_plane : a.d_units, lo, ch);
+    } else if (sg.equal_units) {                           // equal blocks: plain division, no search
+        fast_divmod(w, a.entry_major ? sg.d_plane : sg.d_units, lo, ch);
     } else {
-        uint32_t hi = a.k;                                 // largest e with prefix[e] <= w
+        uint32_t hi = sg.k;                                // largest e with prefix[e] <= w
         while (hi - lo > 1) {
             const uint32_t mid = (lo + hi) >> 1;
             if (prefix[mid] <= w) lo = mid;
@@ -410,11 +493,11 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
         }
         ch = w - prefix[lo];
     }
-    const DevEntry en = table[lo];
+    const DevEntry en = table[sg.first_entry + lo];
     if (a.entry_major) {                                   // ch still counts (rank, unit) inside the plane
-        const FastDiv by_units = a.equal_units
-                                     ? a.d_units
-                                     : FastDiv{prefix[a.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
+        const FastDiv by_units = sg.equal_units
+                                     ? sg.d_units
+                                     : FastDiv{prefix[sg.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
         const uint32_t in_plane = ch;
         fast_divmod(in_plane, by_units, R, ch);
     }
@@ -431,7 +514,7 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     }
     const uint64_t src = block_address(en.src, srcR, en.src_stride);
     const uint64_t dst = block_address(en.dst, R, en.dst_stride);
-    switch (en.meta & 0xFFu) {
+    switch (sg.width_log2) {                               // uniform: one path per workgroup
         case 4: move_unit<vec16_t, NTL>(dst, src, unit_offset<vec16_t>(ch, en.last_offset)); break;
         case 3: move_unit<vec8_t, false>(dst, src, unit_offset<vec8_t>(ch, en.last_offset)); break;
         case 2: move_unit<uint32_t, false>(dst, src, unit_offset<uint32_t>(ch, en.last_offset)); break;
@@ -442,9 +525,17 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
 
 // Shift rounds of equal blocks on a mesh: the shift kernel's decomposition (no prefix search, no
 // per-entry unit width) with the mesh's validity test.  Field names match what mesh_source_rank reads.
+//
+// Most ranks of a mesh are interior: every move of the launch has a source there.  The host marks,
+// one bit per tile, the tiles all of whose ranks are interior; such a workgroup skips the per-lane
+// decode of all coordinates and the loads of the reference offsets and does what the torus kernel
+// does.  (Deciding this in the kernel from the tile's first and last rank costs as much as it
+// saves: the test is a chain of dependent scalar loads of launch constants, and what bounds these
+// kernels is how long a wavefront holds its slot before its one load is under way.)
 struct MeshArgs {
     const DevEntry *entries;
     const uint32_t *offsets;   // [s][d] effective coordinates
+    const uint32_t *interior;  // bit t: every rank of tile t has a source for every entry of the launch
     TileMap map;
     uint32_t total, k;
     uint32_t inner, pj;        // rank stride and size of the moving dimension (1, 1 for a same-rank copy)
@@ -453,7 +544,7 @@ struct MeshArgs {
     int32_t d;
     uint32_t periodic_mask;
     static constexpr uint32_t vector_round = 0;
-    FastDiv d_chunks, d_k, d_p;
+    FastDiv d_chunks, d_k, d_p, d_inner, d_pj;
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
     uint64_t last_offset;
@@ -465,6 +556,7 @@ __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshAr
     const EntryTable<LDS> table(a.entries, a.k, lds);
     uint32_t tile;
     if (!tile_of_block(a.map, tile)) return;
+    const bool interior = (a.interior[tile >> 5] >> (tile & 31u)) & 1u;      // uniform: one scalar load
     const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
@@ -473,7 +565,18 @@ __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshAr
     else fast_divmod(t, a.d_k, R, e);
     const DevEntry en = table[e];
     uint32_t srcR = R;
-    if (!mesh_source_rank(a, en, R, srcR)) return;        // no source: leave the destination as it is
+    if (interior) {                                       // every move has its source: the torus kernel's path
+        if (a.shift_dim >= 0) {
+            srcR -= en.shift * a.inner;
+            if ((a.periodic_mask >> a.shift_dim) & 1u) {  // the moving dimension wraps
+                const uint32_t q = fast_div(R, a.d_inner);
+                const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
+                if (rj < en.shift) srcR += a.pj * a.inner;
+            }
+        }
+    } else if (!mesh_source_rank(a, en, R, srcR)) {
+        return;                                           // no source: leave the destination as it is
+    }
     move_unit<V, NTL>(block_address(en.dst, R, en.dst_stride), block_address(en.src, srcR, en.src_stride),
                       unit_offset_if<V, TAIL>(ch, a.last_offset));
 }

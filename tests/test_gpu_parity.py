@@ -385,3 +385,26 @@ def test_config5_full_size(alg):
         info = _check_full(cfg, op, alg, cfg.m, seed=5005, host_oracle=False)
         torch.cuda.empty_cache()
     assert info["delivered_bytes"] == cfg.p * cfg.s * cfg.m
+
+
+@pytest.mark.parametrize("mode", [iso.ISO_SX_LAUNCHES, iso.ISO_SX_FUSED])
+def test_sx_init_calls_are_the_straightforward_algorithm(mode):
+    """iso_neighbor_{alltoall,allgather}_sx_init: s launches or one, no workspace, the oracle's bytes."""
+    dims, offsets, m = (7, 5, 6), gen.positive_octant(3, 3), 48
+    p, s = int(np.prod(dims)), len(offsets)
+    comm = _comm(dims, offsets)
+    a2a_h, ag_h = gen.alltoall_send(31, p, s, m), gen.allgather_send(31, p, m)
+    for init, send_h, want in ((iso.iso_neighbor_alltoall_sx_init, a2a_h, orc.alltoall(dims, offsets, a2a_h)),
+                               (iso.iso_neighbor_allgather_sx_init, ag_h, orc.allgather(dims, offsets, ag_h))):
+        send = torch.from_numpy(send_h).to(DEV)
+        recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=DEV)
+        req = init(send, recv, m, mode, comm)
+        info = iso.iso_request_info(req)
+        assert info["launches"] == (s if mode == iso.ISO_SX_LAUNCHES else 1) and info["workspace_bytes"] == 0
+        assert info["algorithm"] == (iso.ISO_ALG_SX_ROUNDS if mode == iso.ISO_SX_LAUNCHES else iso.ISO_ALG_SX_FUSED)
+        iso.iso_start(req)
+        iso.iso_request_free(req)                  # waits for the collective before it frees the table
+        assert np.array_equal(recv.cpu().numpy(), want)
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_neighbor_alltoall_sx_init(send, recv, m, 7, comm)
+    assert e.value.status == iso.ISO_ERR_ARG

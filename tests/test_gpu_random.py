@@ -18,9 +18,17 @@ TORUS_ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_R
 MESH_ALGS = TORUS_ALGS[:4]
 
 
-def _case(rng, mesh):
-    d = int(rng.integers(1, 5))
-    dims = tuple(int(x) for x in rng.integers(1, 10, size=d))
+def _case(rng, mesh, d=None):
+    """d given: a torus or mesh of that many dimensions with sizes 1..3 and at most 4096 ranks
+    (more dimensions than the kernels' unrolled coordinate decodes cover)."""
+    if d is None:
+        d = int(rng.integers(1, 5))
+        dims = tuple(int(x) for x in rng.integers(1, 10, size=d))
+    else:
+        while True:
+            dims = tuple(int(x) for x in rng.choice([1, 2, 2, 2, 3], size=d))
+            if 64 <= int(np.prod(dims)) <= 4096:
+                break
     s = int(rng.integers(1, 20))
     span = int(rng.integers(1, 6))
     offsets = [tuple(int(x) for x in rng.integers(-span, span + 1, size=d)) for _ in range(s)]
@@ -48,7 +56,22 @@ def _run(comm, op, alg, m, send, p, s):
 @pytest.mark.parametrize("seed", range(24))
 def test_random_torus_every_byte(seed):
     rng = np.random.default_rng(5000 + seed)
-    dims, _, offsets, m = _case(rng, mesh=False)
+    _torus_body(seed, *_case(rng, mesh=False))
+
+
+@pytest.mark.parametrize("d", [7, 8, 11, 16])
+def test_many_dimensions_every_byte(d):
+    """Tori and meshes with more dimensions than the coordinate decodes are unrolled for (6):
+    the run-time-indexed decodes of the s-exchange, mesh and block kernels."""
+    for seed in (0, 1):
+        rng = np.random.default_rng(8000 + 10 * d + seed)
+        _torus_body(seed, *_case(rng, mesh=False, d=d))
+        _mesh_body(seed, *_case(rng, mesh=True, d=d))
+        _irregular_body(rng, False, *_case(rng, mesh=False, d=d)[:3])
+        _irregular_body(rng, True, *_case(rng, mesh=True, d=d)[:3])
+
+
+def _torus_body(seed, dims, _, offsets, m):
     p, s = int(np.prod(dims)), len(offsets)
     comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, len(dims)))
     a2a_h, ag_h = gen.alltoall_send(seed, p, s, m), gen.allgather_send(seed, p, m)
@@ -65,7 +88,10 @@ def test_random_torus_every_byte(seed):
 @pytest.mark.parametrize("seed", range(16))
 def test_random_mesh_every_byte(seed):
     rng = np.random.default_rng(6000 + seed)
-    dims, periodic, offsets, m = _case(rng, mesh=True)
+    _mesh_body(seed, *_case(rng, mesh=True))
+
+
+def _mesh_body(seed, dims, periodic, offsets, m):
     p, s = int(np.prod(dims)), len(offsets)
     comm = iso.iso_neighborhood_create_mesh(dims, periodic, np.asarray(offsets, np.int32).reshape(s, len(dims)))
     a2a_h, ag_h = gen.alltoall_send(seed, p, s, m), gen.allgather_send(seed, p, m)
@@ -103,6 +129,10 @@ def test_random_irregular_every_byte(seed):
     rng = np.random.default_rng(7000 + seed)
     mesh = seed % 2 == 1
     dims, periodic, offsets, _ = _case(rng, mesh)
+    _irregular_body(rng, mesh, dims, periodic, offsets)
+
+
+def _irregular_body(rng, mesh, dims, periodic, offsets):
     d, p, s = len(dims), int(np.prod(dims)), len(offsets)
     arr = np.asarray(offsets, np.int32).reshape(s, d)
     comm = iso.iso_neighborhood_create_mesh(dims, periodic, arr) if mesh else iso.iso_neighborhood_create(dims, arr)

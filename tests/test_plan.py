@@ -424,9 +424,15 @@ def test_onehop_is_refused_on_a_mesh_and_full_periodicity_is_the_torus():
 
 # ---------------------------------------------------------------- seeded random sweep
 
-def _random_case(rng, mesh):
-    d = int(rng.integers(1, 5))
-    dims = tuple(int(x) for x in rng.integers(1, 6, size=d))
+def _random_case(rng, mesh, d=None):
+    if d is None:
+        d = int(rng.integers(1, 5))
+        dims = tuple(int(x) for x in rng.integers(1, 6, size=d))
+    else:                       # many dimensions, few ranks
+        while True:
+            dims = tuple(int(x) for x in rng.choice([1, 2, 2, 3], size=d))
+            if int(np.prod(dims)) <= 1024:
+                break
     s = int(rng.integers(0, 13))
     span = int(rng.integers(1, 8))
     offsets = [tuple(int(x) for x in rng.integers(-span, span + 1, size=d)) for _ in range(s)]
@@ -439,13 +445,13 @@ def _random_case(rng, mesh):
     return dims, periodic, offsets
 
 
-@pytest.mark.parametrize("seed", range(40))
+@pytest.mark.parametrize("seed", range(48))
 def test_random_torus_plans_reach_the_oracle_result(seed):
     """Random tori (sizes 1..5, so offsets alias and wrap several times), random signed
     offsets with repeats and zero vectors: every algorithm's plan, replayed on the host,
-    gives the definition, without hazards."""
+    gives the definition, without hazards.  Seeds from 40 on: 7 to 16 dimensions."""
     rng = np.random.default_rng(1000 + seed)
-    dims, _, offsets = _random_case(rng, mesh=False)
+    dims, _, offsets = _random_case(rng, mesh=False, d=None if seed < 40 else (7, 8, 9, 10, 12, 14, 16, 16)[seed - 40])
     p, s, m = int(np.prod(dims)), len(offsets), 2
     comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, len(dims)))
     a2a = rng.integers(0, 256, size=(p, s, m), dtype=np.uint8)
@@ -460,10 +466,10 @@ def test_random_torus_plans_reach_the_oracle_result(seed):
             assert {(iso.ISO_BUF_RECV, i) for i in range(s)} <= written
 
 
-@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("seed", range(36))
 def test_random_mesh_plans_reach_the_oracle_result(seed):
     rng = np.random.default_rng(2000 + seed)
-    dims, periodic, offsets = _random_case(rng, mesh=True)
+    dims, periodic, offsets = _random_case(rng, mesh=True, d=None if seed < 30 else (7, 8, 10, 12, 16, 16)[seed - 30])
     p, s, m = int(np.prod(dims)), len(offsets), 2
     comm = iso.iso_neighborhood_create_mesh(dims, periodic, np.asarray(offsets, np.int32).reshape(s, len(dims)))
     a2a = rng.integers(0, 256, size=(p, s, m), dtype=np.uint8)
@@ -479,6 +485,27 @@ def test_random_mesh_plans_reach_the_oracle_result(seed):
             got = _replay_mesh(dims, periodic, offsets, op, order, _plan_rounds(plan), pinfo["work_slots"],
                                send, m)
             assert np.array_equal(got, want), (dims, periodic, offsets, alg, op)
+
+
+def test_workspace_names_of_the_message_combining_schedule():
+    comm = iso.iso_neighborhood_create((9, 9, 9), gen.positive_octant(3, 3))
+    for m in (0, 1, 48, 4096):
+        assert iso.iso_alltoall_workspace_bytes(comm, m) == \
+            iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m)
+        assert iso.iso_allgather_workspace_bytes(comm, m) == \
+            iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED, m)
+    assert iso.iso_alltoall_workspace_bytes(comm, 16) > 0
+    fig1 = iso.iso_neighborhood_create((9, 9, 9), [(0, 0, 0), (0, 0, 1), (1, 0, 0), (1, 1, 0), (1, 1, 1), (3, 2, 0),
+                                                    (3, 3, 2), (4, 0, 1), (4, 0, 2), (4, 1, 1)])
+    assert iso.iso_allgather_workspace_bytes(fig1, 16) == 4 * 729 * 16       # Figure 1: four stored nodes are no neighbours
+    # irregular allgather: every process sends one size, as the init call demands
+    s = len(gen.positive_octant(3, 3))
+    assert iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED, [24] * s) == \
+        iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED, 24)
+    with pytest.raises(iso.IsoError) as e:
+        iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED, [24] * (s - 1) + [25])
+    assert e.value.status == iso.ISO_ERR_ARG
+    iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, [24] * (s - 1) + [25])
 
 
 def test_sizes_that_would_overflow_are_refused():
