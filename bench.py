@@ -51,7 +51,9 @@ def parse():
     ap.add_argument("--mesh", action="store_true", help="the torus taken as a box: no dimension wraps (Section 7)")
     ap.add_argument("--irregular", type=int, default=0, metavar="BASE",
                     help="all-to-all with the stencil block sizes of Section 4: BASE^(d - |C|_1) bytes per neighbour")
-    ap.add_argument("--graph", action="store_true", help="replay the timed requests as HIP graphs")
+    ap.add_argument("--graph", type=int, default=0, choices=(0, 1, 2),
+                    help="replay the timed requests as HIP graphs: 1 = chain of kernel nodes, 2 = rounds of one "
+                         "dimension as parallel branches")
     ap.add_argument("--seed", type=int, default=2016)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the comparison algorithms and the copy ceiling")
@@ -112,7 +114,7 @@ def small_sweep():
                 wsb = iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, m)
                 work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                 req = iso.iso_neighbor_alltoall_init(send, recv, m, work, comm, alg)
-                for graph in (False, True):
+                for graph in (iso.ISO_GRAPH_OFF, iso.ISO_GRAPH_CHAIN):
                     iso.iso_request_set_graph(req, graph)
                     for _ in range(10):
                         iso.iso_start(req, stream)
@@ -233,7 +235,7 @@ class Bench:
         self.launches = sum(i["launches"] for i in self.infos)
         if args.graph:
             for r in self.reqs:
-                iso.iso_request_set_graph(r, True)
+                iso.iso_request_set_graph(r, args.graph)
 
     # -- requests ------------------------------------------------------------------
     def make_request(self, op, alg, timed_buffers=False):
@@ -479,13 +481,14 @@ class Bench:
         for op, r in zip(ops, self.reqs):
             ms = self.time_steps([r], ksteps, 3) / ksteps
             extras[f"combined_{self.op_name[op]}_only"] = rate([r], ms)
-        for r in self.reqs:                                  # the same requests replayed as HIP graphs
-            iso.iso_request_set_graph(r, True)
-        ms = self.time_steps(self.reqs, ksteps, 3) / ksteps
-        extras["combined_graph"] = rate(self.reqs, ms)
-        extras["combined_graph"]["launches"] = len(self.reqs)
+        for form, name in ((iso.ISO_GRAPH_CHAIN, "combined_graph_chain"), (iso.ISO_GRAPH_BRANCHES, "combined_graph_branches")):
+            for r in self.reqs:                              # the same requests replayed as HIP graphs
+                iso.iso_request_set_graph(r, form)
+            ms = self.time_steps(self.reqs, ksteps, 3) / ksteps
+            extras[name] = rate(self.reqs, ms)
+            extras[name]["launches"] = len(self.reqs)
         for r in self.reqs:
-            iso.iso_request_set_graph(r, False)
+            iso.iso_request_set_graph(r, iso.ISO_GRAPH_OFF)
         extras["copy_1GiB_GBs_read_plus_write"] = self.copy_reference_rate()
         # irregular all-to-all in the shape of the paper's stencil experiment (Section 4): block of
         # neighbour i has base^(d - ||C^i||_1) bytes; same torus, Moore radius 1, base 64

@@ -328,12 +328,22 @@ int iso_start(iso_request_t req, void *hip_stream);
  * order (0 <= first, first+count <= launches of iso_request_info).  For timing
  * individual rounds; running all ranges in order equals one iso_start. */
 int iso_start_range(iso_request_t req, int first, int count, void *hip_stream);
-/* enable != 0: records the request's launch sequence once into a HIP graph (one
- * kernel node per round, chained; allocates the graph on first use) and makes
- * every later iso_start replay that graph with a single hipGraphLaunch -- the
- * persistent request of Section 2 taken one step further, for collectives whose
- * cost is dominated by the per-round start-up.  enable == 0: back to individual
- * launches.  iso_start_range is unaffected.  The result is the same either way. */
+/* Replays the request's launches as a HIP graph: the persistent request of
+ * Section 2 taken one step further, for collectives whose cost is dominated by
+ * the per-round start-up.  enable (enum iso_graph_form):
+ *   ISO_GRAPH_OFF      back to individual launches;
+ *   ISO_GRAPH_CHAIN    one kernel node per launch, each after the one before;
+ *   ISO_GRAPH_BRANCHES one kernel node per launch with an edge only where a later
+ *                      launch reads or overwrites blocks an earlier one wrote, or
+ *                      overwrites blocks it read: the rounds of one dimension,
+ *                      which move disjoint blocks, become parallel branches.
+ * The graph is built on the first call that asks for a form and replayed by every
+ * later iso_start with one hipGraphLaunch; asking for the other form waits for
+ * the request's last start and rebuilds.  iso_start_range is unaffected.  The
+ * result is the same in every form.  (On the ROCm 7.2 runtime neither form is
+ * faster than individual launches: a graph launch costs more than the launches
+ * it replaces, and every join of branches adds 8 to 20 microseconds.) */
+enum iso_graph_form { ISO_GRAPH_OFF = 0, ISO_GRAPH_CHAIN = 1, ISO_GRAPH_BRANCHES = 2 };
 int iso_request_set_graph(iso_request_t req, int enable);
 /* Blocks the host until the most recent iso_start / iso_start_range of this
  * request completed (Section 7's proposed completion call).  Only the stream of

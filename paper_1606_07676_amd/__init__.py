@@ -9,7 +9,7 @@ from .binding import (  # noqa: F401
     ISO_OP_ALLTOALL, ISO_OP_ALLGATHER,
     ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP,
     ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK,
-    ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR, ISO_SX_LAUNCHES, ISO_SX_FUSED,
+    ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR, ISO_SX_LAUNCHES, ISO_SX_FUSED, ISO_GRAPH_OFF, ISO_GRAPH_CHAIN, ISO_GRAPH_BRANCHES,
     iso_alltoall_workspace_bytes, iso_allgather_workspace_bytes,
     iso_neighbor_alltoall_sx_init, iso_neighbor_allgather_sx_init,
     ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR,

@@ -19,6 +19,7 @@ ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, I
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
 ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR = 0, 1
 ISO_SX_LAUNCHES, ISO_SX_FUSED = 0, 1
+ISO_GRAPH_OFF, ISO_GRAPH_CHAIN, ISO_GRAPH_BRANCHES = 0, 1, 2
 ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR = 0, 1, 2
 
 
@@ -484,7 +485,8 @@ def iso_start_range(req, first, count, stream=None):
 
 
 def iso_request_set_graph(req, enable=True):
-    _check(load_library().iso_request_set_graph(req.handle, 1 if enable else 0), "iso_request_set_graph")
+    """enable: False / True (= ISO_GRAPH_CHAIN) or one of ISO_GRAPH_OFF / _CHAIN / _BRANCHES."""
+    _check(load_library().iso_request_set_graph(req.handle, int(enable)), "iso_request_set_graph")
 
 
 def iso_wait(req):

@@ -40,6 +40,7 @@ struct iso_request_s {
     bool started = false;
     hipGraph_t graph = nullptr;          // the launches of one collective as a HIP graph
     hipGraphExec_t graph_exec = nullptr;
+    int graph_form = 0;                  // ISO_GRAPH_CHAIN or ISO_GRAPH_BRANCHES: what `graph` was built as
     bool use_graph = false;
 };
 
@@ -526,39 +527,72 @@ int iso_neighbor_alltoall_noalloc(const void *sendbuf, void *recvbuf, size_t m, 
 }
 
 int iso_request_set_graph(iso_request_t req, int enable) {
-    if (!req) return ISO_ERR_ARG;
+    if (!req || enable < 0 || enable > ISO_GRAPH_BRANCHES) return ISO_ERR_ARG;
     if (!enable || req->b.launches.empty()) {
         req->use_graph = false;
         return ISO_SUCCESS;
     }
+    if (req->graph_exec && req->graph_form != enable) {       // the other form was built before: replace it
+        ISO_HIP_TRY(hipStreamSynchronize(req->last_stream));
+        (void)hipGraphExecDestroy(req->graph_exec);
+        (void)hipGraphDestroy(req->graph);
+        req->graph_exec = nullptr;
+        req->graph = nullptr;
+    }
     if (!req->graph_exec) {
-        // record the launch sequence once on a private stream, then replay it
-        hipStream_t cs = nullptr;
-        ISO_HIP_TRY(hipStreamCreateWithFlags(&cs, hipStreamNonBlocking));
-        hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeRelaxed);
-        int st = ISO_SUCCESS;
-        if (e == hipSuccess) {
-            for (const iso::Launch &l : req->b.launches)
-                if ((st = iso::enqueue(req->b.info.vector_bytes, l, cs)) != ISO_SUCCESS) break;
-            hipGraph_t g = nullptr;
-            e = hipStreamEndCapture(cs, &g);
-            if (e == hipSuccess && st == ISO_SUCCESS) {
-                e = hipGraphInstantiate(&req->graph_exec, g, nullptr, nullptr, 0);
-                req->graph = g;
-            } else if (g) {
-                (void)hipGraphDestroy(g);
+        // One kernel node per launch.  ISO_GRAPH_CHAIN: every node after the one before it.
+        // ISO_GRAPH_BRANCHES: an edge from an earlier launch only where the two touch a common block and
+        // one of them writes it (the send buffer is never written): the rounds of one dimension move
+        // disjoint blocks and become parallel branches, a round of the next dimension waits only for the
+        // rounds that delivered what it forwards.
+        const std::vector<iso::Round> &rounds = req->b.plan.rounds;
+        auto conflict = [&](int ra, int rb) {
+            for (const iso_plan_entry_t &x : rounds[(size_t)ra].entries)
+                for (const iso_plan_entry_t &y : rounds[(size_t)rb].entries) {
+                    const bool x_writes_what_y_touches =
+                        (x.dst_buf == y.dst_buf && x.dst_slot == y.dst_slot) ||
+                        (x.dst_buf == y.src_buf && x.dst_slot == y.src_slot);
+                    const bool y_writes_what_x_reads = y.dst_buf == x.src_buf && y.dst_slot == x.src_slot;
+                    if (x_writes_what_y_touches || y_writes_what_x_reads) return true;
+                }
+            return false;
+        };
+        hipGraph_t g = nullptr;
+        ISO_HIP_TRY(hipGraphCreate(&g, 0));
+        std::vector<hipGraphNode_t> nodes(req->b.launches.size());
+        hipError_t e = hipSuccess;
+        for (size_t i = 0; i < req->b.launches.size() && e == hipSuccess; ++i) {
+            const iso::Launch &l = req->b.launches[i];
+            std::vector<hipGraphNode_t> deps;
+            if (enable == ISO_GRAPH_CHAIN) {
+                if (i) deps.push_back(nodes[i - 1]);
+            } else {
+                for (size_t j = 0; j < i; ++j) {
+                    const int rj = req->b.launches[j].round;
+                    if (rj != l.round && conflict(rj, l.round)) deps.push_back(nodes[j]);
+                }
             }
+            const iso::KernelRef k = iso::select_kernel(req->b.info.vector_bytes, l);
+            void *args[1] = {const_cast<void *>(k.arg)};
+            hipKernelNodeParams np{};
+            np.func = const_cast<void *>(k.func);
+            np.gridDim = dim3(l.grid);
+            np.blockDim = dim3(iso::kThreads);
+            np.sharedMemBytes = 0;
+            np.kernelParams = args;
+            np.extra = nullptr;
+            e = hipGraphAddKernelNode(&nodes[i], g, deps.empty() ? nullptr : deps.data(), deps.size(), &np);
         }
-        (void)hipStreamDestroy(cs);
-        if (st != ISO_SUCCESS) return st;
+        if (e == hipSuccess) e = hipGraphInstantiate(&req->graph_exec, g, nullptr, nullptr, 0);
         if (e != hipSuccess) {
-            if (req->graph) (void)hipGraphDestroy(req->graph);
-            req->graph = nullptr;
+            (void)hipGraphDestroy(g);
             req->graph_exec = nullptr;
             g_last_hip_error = (int)e;
             (void)hipGetLastError();
             return ISO_ERR_HIP;
         }
+        req->graph = g;
+        req->graph_form = enable;
     }
     req->use_graph = true;
     return ISO_SUCCESS;

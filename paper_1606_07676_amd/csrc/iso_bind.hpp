@@ -41,6 +41,7 @@ struct Launch {
     bool stream_loads;     // every source block is read exactly once in this launch: non-temporal loads
     bool tail;             // regular kernels: the last unit of a block overlaps the one before it
     bool uniform_waves;    // shift kernel, 16-byte units, blocks a multiple of 64 units: one block per wavefront
+    int round;             // the plan's round this launch belongs to (a large round is split over several launches)
 
     ShiftArgs shift;
     VectorArgs vec;
@@ -198,78 +199,70 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k, bool eighths) {
     }
 }
 
+// Which instantiation runs a launch, and the argument struct it takes: resolved once per launch,
+// used both for plain launches and for the kernel nodes of a request's graph.
+struct KernelRef {
+    const void *func;
+    const void *arg;
+};
+
 // Streaming loads exist for the shift kernel at the 16-byte width only (narrower
 // units are the slow path anyway).
 template <typename V, bool LDS, bool TAIL>
-void enqueue_regular(const Launch &l, hipStream_t stream) {
-    const dim3 grid(l.grid), block(kThreads);
-    if (l.kernel == kVectorKernel) {
-        hipLaunchKernelGGL((vector_round_kernel<V, LDS, TAIL>), grid, block, 0, stream, l.vec);
-        return;
-    }
+KernelRef select_regular(const Launch &l) {
+    if (l.kernel == kVectorKernel) return {(const void *)&vector_round_kernel<V, LDS, TAIL>, &l.vec};
     if (l.kernel == kMeshShiftKernel) {
         if constexpr (sizeof(V) == 16) {
-            if (l.stream_loads) {
-                hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, true, TAIL>), grid, block, 0, stream, l.mesh_shift);
-                return;
-            }
+            if (l.stream_loads) return {(const void *)&mesh_shift_round_kernel<V, LDS, true, TAIL>, &l.mesh_shift};
         }
-        hipLaunchKernelGGL((mesh_shift_round_kernel<V, LDS, false, TAIL>), grid, block, 0, stream, l.mesh_shift);
-        return;
+        return {(const void *)&mesh_shift_round_kernel<V, LDS, false, TAIL>, &l.mesh_shift};
     }
     if constexpr (sizeof(V) == 16) {
         if (l.uniform_waves) {
-            if (l.stream_loads) hipLaunchKernelGGL((shift_round_uniform_kernel<true>), grid, block, 0, stream, l.shift);
-            else hipLaunchKernelGGL((shift_round_uniform_kernel<false>), grid, block, 0, stream, l.shift);
-            return;
+            if (l.stream_loads) return {(const void *)&shift_round_uniform_kernel<true>, &l.shift};
+            return {(const void *)&shift_round_uniform_kernel<false>, &l.shift};
         }
-        if (l.stream_loads) {
-            hipLaunchKernelGGL((shift_round_kernel<V, LDS, true, TAIL>), grid, block, 0, stream, l.shift);
-            return;
-        }
+        if (l.stream_loads) return {(const void *)&shift_round_kernel<V, LDS, true, TAIL>, &l.shift};
     }
-    hipLaunchKernelGGL((shift_round_kernel<V, LDS, false, TAIL>), grid, block, 0, stream, l.shift);
+    return {(const void *)&shift_round_kernel<V, LDS, false, TAIL>, &l.shift};
 }
 
 template <typename V>
-void enqueue_width(const Launch &l, hipStream_t stream) {
+KernelRef select_width(const Launch &l) {
     if constexpr (sizeof(V) > 1) {
         if (l.tail) {                     // the unit width does not divide the block size
-            if (l.lds_table) enqueue_regular<V, true, true>(l, stream);
-            else enqueue_regular<V, false, true>(l, stream);
-            return;
+            if (l.lds_table) return select_regular<V, true, true>(l);
+            return select_regular<V, false, true>(l);
         }
     }
-    if (l.lds_table) enqueue_regular<V, true, false>(l, stream);
-    else enqueue_regular<V, false, false>(l, stream);
+    if (l.lds_table) return select_regular<V, true, false>(l);
+    return select_regular<V, false, false>(l);
 }
 
 template <bool LDS, bool MESH>
-void enqueue_block(const Launch &l, hipStream_t stream) {
-    const dim3 grid(l.grid), block(kThreads);
-    if (l.stream_loads) hipLaunchKernelGGL((block_round_kernel<LDS, MESH, true>), grid, block, 0, stream, l.block);
-    else hipLaunchKernelGGL((block_round_kernel<LDS, MESH, false>), grid, block, 0, stream, l.block);
+KernelRef select_block(const Launch &l) {
+    if (l.stream_loads) return {(const void *)&block_round_kernel<LDS, MESH, true>, &l.block};
+    return {(const void *)&block_round_kernel<LDS, MESH, false>, &l.block};
+}
+
+inline KernelRef select_kernel(int vector_bytes, const Launch &l) {
+    if (l.kernel == kBlockKernel) {
+        if (l.mesh) return l.lds_table ? select_block<true, true>(l) : select_block<false, true>(l);
+        return l.lds_table ? select_block<true, false>(l) : select_block<false, false>(l);
+    }
+    switch (vector_bytes) {
+        case 16: return select_width<vec16_t>(l);
+        case 8:  return select_width<vec8_t>(l);
+        case 4:  return select_width<uint32_t>(l);
+        case 2:  return select_width<uint16_t>(l);
+        default: return select_width<uint8_t>(l);
+    }
 }
 
 inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
-    if (l.kernel == kBlockKernel) {
-        if (l.mesh) {
-            if (l.lds_table) enqueue_block<true, true>(l, stream);
-            else enqueue_block<false, true>(l, stream);
-        } else {
-            if (l.lds_table) enqueue_block<true, false>(l, stream);
-            else enqueue_block<false, false>(l, stream);
-        }
-    } else {
-        switch (vector_bytes) {
-            case 16: enqueue_width<vec16_t>(l, stream); break;
-            case 8:  enqueue_width<vec8_t>(l, stream); break;
-            case 4:  enqueue_width<uint32_t>(l, stream); break;
-            case 2:  enqueue_width<uint16_t>(l, stream); break;
-            default: enqueue_width<uint8_t>(l, stream); break;
-        }
-    }
-    ISO_HIP_TRY(hipGetLastError());
+    const KernelRef k = select_kernel(vector_bytes, l);
+    void *args[1] = {const_cast<void *>(k.arg)};
+    ISO_HIP_TRY(hipLaunchKernel(k.func, dim3(l.grid), dim3(kThreads), args, 0, stream));
     return ISO_SUCCESS;
 }
 
@@ -445,6 +438,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             pd.first_prefix = prefixes.size();
             Launch &l = pd.l;
             std::memset(&l, 0, sizeof(l));
+            l.round = (int)ri;
             uint32_t k = 0;
             uint64_t total = 0;
             if (uniform && (!c.mesh || r.kind != ISO_ROUND_VECTOR)) {

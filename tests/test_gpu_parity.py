@@ -188,7 +188,7 @@ def test_restart_and_side_stream_give_the_same_result():
 @pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS],
                          ids=lambda a: ALG_NAMES[a])
 def test_graph_replay_matches_eager_every_time(alg):
-    """The captured launch sequence is replayed several times, with eager work of this
+    """The request's graph (both forms) is replayed several times, with eager work of this
     program (fills, another eager collective) and synchronisations in between; every
     replay must give the oracle's result."""
     cases = [((8, 8), gen.moore(2, 1), 32, iso.ISO_OP_ALLTOALL),
@@ -211,8 +211,9 @@ def test_graph_replay_matches_eager_every_time(alg):
         recv = torch.empty((p, s, m), dtype=torch.uint8, device=DEV)
         work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
         req = init(send, recv, m, work, comm, alg)
-        iso.iso_request_set_graph(req, True)
-        for rep in range(4):
+        for rep in range(6):
+            # replays 0-2 as a chain of kernel nodes, 3-5 with the rounds of a dimension as parallel branches
+            iso.iso_request_set_graph(req, iso.ISO_GRAPH_CHAIN if rep < 3 else iso.ISO_GRAPH_BRANCHES)
             recv.fill_(0xEE)                       # eager work between replays
             work.fill_(0xDD)
             other, _ = _run(dims, offsets, op, iso.ISO_ALG_SX_FUSED, m, send)     # an eager collective
