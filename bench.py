@@ -44,7 +44,7 @@ def parse():
     ap.add_argument("--m", type=int, default=None, help="override the block size in bytes (with --config)")
     ap.add_argument("--layout", choices=("rank", "slot"), default="rank",
                     help="buffers of the timed requests: rank = the paper's [p][s][m] (default), slot = [s][p][m]")
-    ap.add_argument("--algorithm", choices=("combined", "bydim", "sx_fused", "sx_rounds", "onehop"),
+    ap.add_argument("--algorithm", choices=("combined", "bydim", "sx_fused", "sx_rounds", "onehop", "staged"),
                     default="combined", help="algorithm of the timed requests (default: combined, one kernel per round)")
     ap.add_argument("--pad", type=int, default=0,
                     help="all-to-all only: every rank's row padded by this many bytes (irregular interface, equal blocks)")
@@ -164,7 +164,7 @@ class Bench:
         self.slot = args.layout == "slot"
         self.alg = {"combined": iso.ISO_ALG_COMBINED, "bydim": iso.ISO_ALG_COMBINED_BYDIM,
                     "sx_fused": iso.ISO_ALG_SX_FUSED, "sx_rounds": iso.ISO_ALG_SX_ROUNDS,
-                    "onehop": iso.ISO_ALG_ONEHOP}[args.algorithm]
+                    "onehop": iso.ISO_ALG_ONEHOP, "staged": iso.ISO_ALG_COMBINED_STAGED}[args.algorithm]
         self.plain = not (args.mesh or args.irregular or args.pad)      # the CPU leg covers these only
         self.op_name = {iso.ISO_OP_ALLTOALL: "alltoall", iso.ISO_OP_ALLGATHER: "allgather"}
         self.ops = [iso.ISO_OP_ALLTOALL if o == "alltoall" else iso.ISO_OP_ALLGATHER for o in cfg.ops]
@@ -668,6 +668,34 @@ class Bench:
         self.torch.cuda.empty_cache()
 
 
+def small_blocks(args, gen, iso):
+    """Config 4 (64^3 torus, Moore radius 1, both collectives) at its small block sizes, where the
+    paper's [p][s][m] rows make a round's writes sparse: the message-combining schedule as it is
+    and regrouped for small blocks (--algorithm staged).  Both are priced on the same algorithmic
+    bytes, those of the message-combining schedule: 2 * (V + W) * p * m per step."""
+    import copy
+    cfg = gen.get_config(4)
+    out = {}
+    for m in (16, 32, 64):
+        row, algorithmic = {}, None
+        for name in ("combined", "staged"):
+            a = copy.copy(args)
+            a.algorithm = name
+            b = Bench(a, cfg, m)
+            if name == "combined":
+                algorithmic = b.moved
+            ms = b.time_steps(b.reqs, args.steps, args.warmup) / args.steps
+            row[name] = {"ms_per_step": round(ms, 5), "launches": b.launches,
+                         "delivered_GBs": round(b.delivered / ms / 1e6, 1),
+                         "algorithmic_GBs": round(algorithmic / ms / 1e6, 1),
+                         "frac_of_peak": round(algorithmic / ms / 1e6 / HBM_PEAK_GBS, 4)}
+            log(f"  small blocks: {cfg.name} m={m} {name}: {ms:.4f} ms/step, "
+                f"{row[name]['frac_of_peak']:.3f} of peak on the schedule's {algorithmic / 1e6:.0f} MB")
+            b.close()
+        out[f"c4_m{m}"] = row
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -699,9 +727,11 @@ def main():
                 (gen.get_config(5), None)]
     results = []
     head_idx = len(todo) - 1
-    if not (args.mesh or args.irregular or args.pad):    # the run's arena, sized for its largest workload
+    plain_run = not (args.mesh or args.irregular or args.pad)
+    if plain_run:                                        # the run's arena, sized for its largest workload
         alg = {"combined": iso.ISO_ALG_COMBINED, "bydim": iso.ISO_ALG_COMBINED_BYDIM, "sx_fused": iso.ISO_ALG_SX_FUSED,
-               "sx_rounds": iso.ISO_ALG_SX_ROUNDS, "onehop": iso.ISO_ALG_ONEHOP}[args.algorithm]
+               "sx_rounds": iso.ISO_ALG_SX_ROUNDS, "onehop": iso.ISO_ALG_ONEHOP,
+               "staged": iso.ISO_ALG_COMBINED_STAGED}[args.algorithm]
         need = 0
         for cfg, m_over in todo:
             comm = iso.iso_neighborhood_create(cfg.dims, cfg.offsets)
@@ -727,6 +757,9 @@ def main():
         results.append(res)
         log(f"  [{time.perf_counter() - t_start:.1f} s since start]")
 
+    small = None
+    if args.config is None and not args.no_extras and plain_run and args.algorithm == "combined" and not args.graph:
+        small = small_blocks(args, gen, iso)
     head = results[head_idx]
     out = {
         "metric": METRIC, "value": head["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -739,6 +772,8 @@ def main():
         out["workloads"] = {r["config"]["profile_tag"]: {k: v for k, v in r.items() if k != "isolated_repetitions"}
                             for r in results}
         out["workloads"][head["config"]["profile_tag"]] = {"see": "top level of this line"}
+    if small:
+        out["small_blocks"] = small
     print(json.dumps(out), flush=True)
 
 

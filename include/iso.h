@@ -72,7 +72,21 @@ enum iso_algorithm {
      * as given (not reduced modulo p_j).  D = sum_j (max+ + max-) launches,
      * V = sum_i ||C^i||_1 block-moves per rank (all-to-all), W (allgather).
      * ISO_ERR_TOO_LARGE if D would exceed 65536. */
-    ISO_ALG_ONEHOP         = 4
+    ISO_ALG_ONEHOP         = 4,
+    /* The message-combining schedule of ISO_ALG_COMBINED for small blocks in the
+     * paper's [p][s][m] layout, where a round that writes a few blocks of every
+     * rank's row costs far more memory traffic than the blocks hold.  The moves are
+     * those of ISO_ALG_COMBINED (same sources, distances and dimensions, same
+     * sum_i nnz(C^i) count for the all-to-all), but the receive buffer is written
+     * by the last launch only: the last hop of every block is taken out of its round
+     * and all of them run as one launch (ISO_ROUND_DELIVER) that gathers, through
+     * LDS, every rank's s blocks and writes whole receive rows.  A move into the
+     * receive buffer that cannot wait (its block is read again, or its source is
+     * overwritten later: allgather trie nodes) goes to an extra workspace slot and is
+     * copied from there by the last launch; the workspace grows by one plane of
+     * p*m bytes per such block.  Rounds left empty disappear.  Not available on a
+     * mesh (ISO_ERR_ARG). */
+    ISO_ALG_COMBINED_STAGED = 5
 };
 
 enum iso_buffer {                /* where a block sits during a schedule */
@@ -85,7 +99,10 @@ enum iso_buffer {                /* where a block sits during a schedule */
 enum iso_round_kind {
     ISO_ROUND_SHIFT  = 0,        /* every entry moves along one dimension (per-entry distance) */
     ISO_ROUND_SELF   = 1,        /* zero offset: same-rank copy send -> recv                   */
-    ISO_ROUND_VECTOR = 2         /* every entry moves by its full offset vector (s-exchange)   */
+    ISO_ROUND_VECTOR = 2,        /* every entry moves by its full offset vector (s-exchange)   */
+    ISO_ROUND_DELIVER = 3        /* last launch of ISO_ALG_COMBINED_STAGED: entry i writes receive
+                                    block i; every entry moves along its own dimension
+                                    (iso_plan_entry_t.dim, -1: same-rank copy)                 */
 };
 
 enum iso_layout {                /* how the p*s blocks of a regular collective lie in a buffer  */
@@ -143,7 +160,9 @@ typedef struct {
                                     valid; equals `neighbor` when that is >= 0).  On a mesh
                                     the move happens at rank R only if R minus C^ref, taken
                                     over the dimensions routed so far, is inside the mesh    */
-    int32_t reserved;
+    int32_t dim;                 /* the dimension the move runs along: the round's for SHIFT
+                                    rounds, the entry's own in a DELIVER round; -1 where the
+                                    entry is a same-rank copy or moves by a full vector     */
 } iso_plan_entry_t;
 
 typedef struct {

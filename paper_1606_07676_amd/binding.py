@@ -16,11 +16,12 @@ ISO_MAX_DIMS = 16
 ISO_NOALLOC_SCRATCH_BYTES, ISO_NOALLOC_TABLE_BYTES = 32 << 20, 256 << 10
 ISO_OP_ALLTOALL, ISO_OP_ALLGATHER = 0, 1
 ISO_ALG_COMBINED, ISO_ALG_COMBINED_BYDIM, ISO_ALG_SX_ROUNDS, ISO_ALG_SX_FUSED, ISO_ALG_ONEHOP = 0, 1, 2, 3, 4
+ISO_ALG_COMBINED_STAGED = 5
 ISO_BUF_SEND, ISO_BUF_RECV, ISO_BUF_WORK = 0, 1, 2
 ISO_LAYOUT_RANK_MAJOR, ISO_LAYOUT_SLOT_MAJOR = 0, 1
 ISO_SX_LAUNCHES, ISO_SX_FUSED = 0, 1
 ISO_GRAPH_OFF, ISO_GRAPH_CHAIN, ISO_GRAPH_BRANCHES = 0, 1, 2
-ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR = 0, 1, 2
+ISO_ROUND_SHIFT, ISO_ROUND_SELF, ISO_ROUND_VECTOR, ISO_ROUND_DELIVER = 0, 1, 2, 3
 
 
 class IsoError(RuntimeError):
@@ -57,7 +58,7 @@ class iso_plan_entry_t(ctypes.Structure):
     _fields_ = [("src_buf", ctypes.c_int32), ("src_slot", ctypes.c_int32),
                 ("dst_buf", ctypes.c_int32), ("dst_slot", ctypes.c_int32),
                 ("shift", ctypes.c_int32), ("neighbor", ctypes.c_int32),
-                ("ref", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("ref", ctypes.c_int32), ("dim", ctypes.c_int32)]
 
 
 class iso_request_info_t(ctypes.Structure):

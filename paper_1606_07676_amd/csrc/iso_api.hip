@@ -578,7 +578,7 @@ int iso_request_set_graph(iso_request_t req, int enable) {
             np.func = const_cast<void *>(k.func);
             np.gridDim = dim3(l.grid);
             np.blockDim = dim3(iso::kThreads);
-            np.sharedMemBytes = 0;
+            np.sharedMemBytes = l.dyn_lds;
             np.kernelParams = args;
             np.extra = nullptr;
             e = hipGraphAddKernelNode(&nodes[i], g, deps.empty() ? nullptr : deps.data(), deps.size(), &np);

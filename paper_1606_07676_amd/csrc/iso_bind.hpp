@@ -31,7 +31,7 @@ constexpr uint32_t kMaxUnits = 0xFFF00000u;   // flat 32-bit work index per laun
         }                                              \
     } while (0)
 
-enum LaunchKernel { kShiftKernel = 0, kVectorKernel = 1, kBlockKernel = 2, kMeshShiftKernel = 3 };
+enum LaunchKernel { kShiftKernel = 0, kVectorKernel = 1, kBlockKernel = 2, kMeshShiftKernel = 3, kDeliverKernel = 4, kStagedRoundKernel = 5 };
 
 struct Launch {
     int kernel;            // LaunchKernel
@@ -42,11 +42,14 @@ struct Launch {
     bool tail;             // regular kernels: the last unit of a block overlaps the one before it
     bool uniform_waves;    // shift kernel, 16-byte units, blocks a multiple of 64 units: one block per wavefront
     int round;             // the plan's round this launch belongs to (a large round is split over several launches)
+    uint32_t dyn_lds;      // bytes of dynamic LDS (the kernels of the staged schedule: their tile)
 
     ShiftArgs shift;
     VectorArgs vec;
     BlockArgs block;
     MeshArgs mesh_shift;
+    DeliverArgs deliver;
+    StagedRoundArgs staged;
 };
 
 // Sizes and displacements (bytes) of the s blocks inside one rank's send and
@@ -177,6 +180,8 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k, bool eighths) {
         l.grid = per_xcd * 8;
     }
     TileMap &tm = l.kernel == kVectorKernel  ? l.vec.map
+                  : l.kernel == kStagedRoundKernel ? l.staged.map
+                  : l.kernel == kDeliverKernel ? l.deliver.map
                   : l.kernel == kBlockKernel ? l.block.map
                   : l.kernel == kMeshShiftKernel ? l.mesh_shift.map
                                                  : l.shift.map;
@@ -184,7 +189,9 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k, bool eighths) {
     tm.run_log2 = run_log2;
     tm.per_xcd = per_xcd;
     l.lds_table = k <= kLdsEntries;
-    if (l.kernel == kVectorKernel) {
+    if (l.kernel == kStagedRoundKernel || l.kernel == kDeliverKernel) {
+        // one tile per workgroup: `total` counts tiles * kThreads here
+    } else if (l.kernel == kVectorKernel) {
         l.vec.total = total;
         l.vec.k = k;
     } else if (l.kernel == kBlockKernel) {
@@ -246,6 +253,14 @@ KernelRef select_block(const Launch &l) {
 }
 
 inline KernelRef select_kernel(int vector_bytes, const Launch &l) {
+    if (l.kernel == kStagedRoundKernel) {                 // blocks of whole 16-byte units only
+        if (l.stream_loads) return {(const void *)&staged_round_kernel<vec16_t, true, kUnitsPerLane>, &l.staged};
+        return {(const void *)&staged_round_kernel<vec16_t, false, kUnitsPerLane>, &l.staged};
+    }
+    if (l.kernel == kDeliverKernel) {
+        if (l.stream_loads) return {(const void *)&deliver_kernel<vec16_t, true, kUnitsPerLane>, &l.deliver};
+        return {(const void *)&deliver_kernel<vec16_t, false, kUnitsPerLane>, &l.deliver};
+    }
     if (l.kernel == kBlockKernel) {
         if (l.mesh) return l.lds_table ? select_block<true, true>(l) : select_block<false, true>(l);
         return l.lds_table ? select_block<true, false>(l) : select_block<false, false>(l);
@@ -262,7 +277,7 @@ inline KernelRef select_kernel(int vector_bytes, const Launch &l) {
 inline int enqueue(int vector_bytes, const Launch &l, hipStream_t stream) {
     const KernelRef k = select_kernel(vector_bytes, l);
     void *args[1] = {const_cast<void *>(k.arg)};
-    ISO_HIP_TRY(hipLaunchKernel(k.func, dim3(l.grid), dim3(kThreads), args, 0, stream));
+    ISO_HIP_TRY(hipLaunchKernel(k.func, dim3(l.grid), dim3(kThreads), args, l.dyn_lds, stream));
     return ISO_SUCCESS;
 }
 
@@ -379,18 +394,54 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
         }
     };
 
+    // The last launch of the staged schedule has a kernel of its own for equal blocks in dense
+    // [p][s][m] receive rows; anywhere else it runs as one launch per dimension on the general kernels.
+    std::vector<Round> bound_rounds;              // the plan's rounds as launched
+    std::vector<int> round_of;                    // their index in the plan
+    bool deliver_rows = false;
+    for (size_t ri = 0; ri < pl.rounds.size(); ++ri) {
+        const Round &r = pl.rounds[ri];
+        if (r.kind != ISO_ROUND_DELIVER) {
+            bound_rounds.push_back(r);
+            round_of.push_back((int)ri);
+            continue;
+        }
+        const uint64_t m0 = s ? lay.size[0] : 0;              // blocks of whole 16-byte units
+        deliver_rows = m0 > 0 && m0 % 16 == 0 && !lay.slot_major && !c.mesh && r.entries.size() == s &&
+                       s <= kLdsEntries && s * (m0 / 16) <= kTileUnits && lay.recv_extent == s * m0;
+        for (size_t i = 0; deliver_rows && i < s; ++i)
+            deliver_rows = lay.size[i] == m0 && lay.recv_displ[i] == i * m0 && r.entries[i].dst_slot == (int)i;
+        if (deliver_rows) {
+            bound_rounds.push_back(r);
+            round_of.push_back((int)ri);
+            continue;
+        }
+        for (int j = -1; j < c.d; ++j) {
+            Round part;
+            part.kind = j < 0 ? ISO_ROUND_SELF : ISO_ROUND_SHIFT;
+            part.dim = j;
+            for (const iso_plan_entry_t &pe : r.entries)
+                if (pe.dim == j) part.entries.push_back(pe);
+            if (part.entries.empty()) continue;
+            bound_rounds.push_back(std::move(part));
+            round_of.push_back((int)ri);
+        }
+    }
+
     // all entries, with their own unit width
-    struct HostEntry { DevEntry de; uint64_t size; };
-    std::vector<std::vector<HostEntry>> rounds(pl.rounds.size());
+    struct HostEntry { DevEntry de; uint64_t size; int dim, dst_slot; };
+    std::vector<std::vector<HostEntry>> rounds(bound_rounds.size());
     bool uniform = true;
     uint64_t size0 = 0;
     uint32_t min_log2 = 4;
     bool first = true;
-    for (size_t ri = 0; ri < pl.rounds.size(); ++ri) {
-        const Round &r = pl.rounds[ri];
+    for (size_t ri = 0; ri < bound_rounds.size(); ++ri) {
+        const Round &r = bound_rounds[ri];
         for (const iso_plan_entry_t &pe : r.entries) {
             HostEntry he{};
             he.size = entry_size(pe);
+            he.dim = pe.dim;
+            he.dst_slot = pe.dst_slot;
             if (he.size == 0) continue;                       // empty blocks make no move
             uint64_t src_stride = 0, dst_stride = 0;
             place(pe.src_buf, pe.src_slot, he.de.src, src_stride);
@@ -428,8 +479,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     std::vector<uint32_t> prefixes;           // irregular launches: k+1 values each
     struct Pending { size_t first_entry, first_prefix; Launch l; };
     std::vector<Pending> pending;
-    for (size_t ri = 0; ri < pl.rounds.size(); ++ri) {
-        const Round &r = pl.rounds[ri];
+    for (size_t ri = 0; ri < bound_rounds.size(); ++ri) {
+        const Round &r = bound_rounds[ri];
         const std::vector<HostEntry> &ents = rounds[ri];
         size_t done = 0;
         while (done < ents.size()) {
@@ -438,10 +489,88 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             pd.first_prefix = prefixes.size();
             Launch &l = pd.l;
             std::memset(&l, 0, sizeof(l));
-            l.round = (int)ri;
+            l.round = round_of[ri];
             uint32_t k = 0;
             uint64_t total = 0;
-            if (uniform && (!c.mesh || r.kind != ISO_ROUND_VECTOR)) {
+            // staged schedule, last launch: whole receive rows through LDS (regular [p][s][m] rows only)
+            const bool deliver = r.kind == ISO_ROUND_DELIVER;         // left as one round only where deliver_rows holds
+            // staged schedule, the rounds: all destinations are planes of the workspace; small equal blocks
+            // are re-tiled through LDS (any round of that schedule whose blocks of one rank fit a tile)
+            const uint32_t st_w = 16;
+            const uint64_t st_upb = size0 / st_w;
+            // (a round between planes only is dense on both sides as it is: the plain kernel, plane after plane)
+            bool all_planes = pl.algorithm == ISO_ALG_COMBINED_STAGED && !deliver && uniform && !c.mesh;
+            for (const HostEntry &he : ents)
+                all_planes = all_planes && he.de.src_stride == size0 && he.de.dst_stride == size0;
+            const bool staged_round = pl.algorithm == ISO_ALG_COMBINED_STAGED && !deliver && !all_planes && uniform &&
+                                      size0 % 16 == 0 &&
+                                      !lay.slot_major && !c.mesh && r.kind != ISO_ROUND_VECTOR && done == 0 &&
+                                      ents.size() <= kLdsEntries && ents.size() * st_upb <= kTileUnits &&
+                                      p * st_upb <= kMaxUnits;
+            if (deliver) {
+                l.kernel = kDeliverKernel;
+                DeliverArgs &da = l.deliver;
+                k = (uint32_t)s;
+                da.p = (uint32_t)p;
+                da.s = (uint32_t)s;
+                da.upb = (uint32_t)st_upb;
+                da.ranks = (uint32_t)std::min<uint64_t>(p, kTileUnits / (s * st_upb));
+                da.dst = (uint64_t)(uintptr_t)recvbuf;
+                while (prefixes.size() % 4) prefixes.push_back(0);            // 16-byte aligned entries
+                pd.first_prefix = prefixes.size();
+                for (int rows = 1; rows >= 0; --rows)                          // rank-major sources first
+                    for (const HostEntry &he : ents) {
+                        if ((he.de.src_stride > size0) != (rows == 1)) continue;
+                        DeliverEntry x{};
+                        x.src = he.de.src;
+                        x.src_stride = he.de.src_stride;
+                        x.slot = (uint32_t)he.dst_slot;
+                        const uint32_t inner = he.dim < 0 ? 1u : (uint32_t)c.inner[(size_t)he.dim];
+                        x.pj = he.dim < 0 ? 1u : (uint32_t)c.dims[(size_t)he.dim];
+                        x.shift = he.dim < 0 ? 0u : he.de.shift;
+                        x.back = x.shift * inner;
+                        x.wrap = x.pj * inner;
+                        x.d_inner = make_fastdiv(inner);
+                        x.d_pj = make_fastdiv(x.pj);
+                        da.k_rows += rows == 1;
+                        const uint32_t *words = (const uint32_t *)&x;
+                        prefixes.insert(prefixes.end(), words, words + sizeof(x) / 4);
+                        table.push_back(he.de);      // keeps the launch's entry count in step with the others
+                    }
+                da.d_upb = make_fastdiv(da.upb);
+                da.d_rows = make_fastdiv(std::max(1u, da.k_rows * da.upb));
+                da.d_plane = make_fastdiv(da.ranks * da.upb);
+                da.d_row = make_fastdiv((uint32_t)(s * st_upb));
+                l.dyn_lds = (uint32_t)(s * ((uint64_t)da.ranks * da.upb + 1) * st_w);
+                total = ((p + da.ranks - 1) / da.ranks) * kThreads;      // set_grid: one workgroup per tile
+            } else if (staged_round) {
+                l.kernel = kStagedRoundKernel;
+                k = (uint32_t)ents.size();
+                StagedRoundArgs &sa = l.staged;
+                // entries that read a rank-major buffer (rank stride larger than the block) first
+                std::vector<size_t> order;
+                for (int rows = 1; rows >= 0; --rows)
+                    for (size_t q = 0; q < ents.size(); ++q)
+                        if ((ents[q].de.src_stride > size0) == (rows == 1)) order.push_back(q);
+                for (size_t q : order) {
+                    table.push_back(ents[q].de);
+                    sa.k_rows += ents[q].de.src_stride > size0;
+                }
+                sa.p = (uint32_t)p;
+                sa.k = k;
+                sa.upb = (uint32_t)st_upb;
+                sa.ranks = (uint32_t)std::min<uint64_t>(p, kTileUnits / (k * st_upb));
+                const bool shift = r.kind == ISO_ROUND_SHIFT;
+                sa.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
+                sa.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
+                sa.d_upb = make_fastdiv(sa.upb);
+                sa.d_row = make_fastdiv(std::max(1u, sa.k_rows * sa.upb));
+                sa.d_plane = make_fastdiv(sa.ranks * sa.upb);
+                sa.d_inner = make_fastdiv(sa.inner);
+                sa.d_pj = make_fastdiv(sa.pj);
+                l.dyn_lds = (uint32_t)(k * ((uint64_t)sa.ranks * sa.upb + 1) * st_w);
+                total = ((p + sa.ranks - 1) / sa.ranks) * kThreads;      // set_grid: one workgroup per tile
+            } else if (uniform && (!c.mesh || r.kind != ISO_ROUND_VECTOR)) {
                 // regular blocks: every entry has `chunks` units of the request's common width
                 // (on a mesh: shift rounds and same-rank copies; its s-exchange uses the block kernel)
                 const uint64_t width = uint64_t(1) << min_log2;
@@ -463,7 +592,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.vec.d_chunks = dch;
                     l.vec.d_k = dk;
                     l.vec.d_p = dp;
-                    l.vec.entry_major = lay.slot_major;
+                    l.vec.entry_major = lay.slot_major || all_planes;
                     l.vec.last_offset = size0 - width;
                     for (int j = 0; j < c.d; ++j) {
                         l.vec.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
@@ -539,7 +668,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.shift.d_chunks = dch;
                     l.shift.d_k = dk;
                     l.shift.d_p = dp;
-                    l.shift.entry_major = lay.slot_major;
+                    l.shift.entry_major = lay.slot_major || all_planes;
                     l.shift.last_offset = size0 - width;
                     l.shift.d_inner = make_fastdiv(l.shift.inner);
                     l.shift.d_pj = make_fastdiv(l.shift.pj);
@@ -622,7 +751,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             // streaming loads: all-to-all shift rounds of equal blocks (irregular blocks and the
             // s-exchange kernels are faster with cacheable loads)
             l.stream_loads = op == ISO_OP_ALLTOALL && r.kind != ISO_ROUND_VECTOR &&
-                             (l.kernel == kShiftKernel || l.kernel == kMeshShiftKernel ||
+                             (l.kernel == kShiftKernel || l.kernel == kMeshShiftKernel || l.kernel == kStagedRoundKernel ||
+                              l.kernel == kDeliverKernel ||
                               (l.kernel == kBlockKernel && l.block.n_segments == 1 && l.block.seg[0].equal_units));
             std::vector<Side> src_sides, dst_sides;
             for (uint32_t q = 0; q < k; ++q) {
@@ -638,20 +768,21 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
 
     // one device allocation: entries, then the [s][d] residues, then the prefix arrays
     const size_t entry_bytes = table.size() * sizeof(DevEntry);
-    const size_t off_bytes = c.can.size() * sizeof(uint32_t);
+    const size_t off_used = c.can.size() * sizeof(uint32_t);
+    const size_t off_bytes = (off_used + 15) & ~size_t(15);     // the prefix arrays start 16-byte aligned
     const size_t pre_bytes = prefixes.size() * sizeof(uint32_t);
     char *dev = nullptr;
     if (arena) {
         if (entry_bytes + off_bytes + pre_bytes > arena->table_bytes) return ISO_ERR_SCRATCH;
         dev = (char *)arena->table;
         if ((st = store_table(*arena, 0, table.data(), entry_bytes)) != ISO_SUCCESS) return st;
-        if ((st = store_table(*arena, entry_bytes, c.can.data(), off_bytes)) != ISO_SUCCESS) return st;
+        if ((st = store_table(*arena, entry_bytes, c.can.data(), off_used)) != ISO_SUCCESS) return st;
         if ((st = store_table(*arena, entry_bytes + off_bytes, prefixes.data(), pre_bytes)) != ISO_SUCCESS) return st;
     } else if (entry_bytes + off_bytes + pre_bytes) {
         ISO_HIP_TRY(hipMalloc(&rq.dev_table, entry_bytes + off_bytes + pre_bytes));
         dev = (char *)rq.dev_table;
         if (entry_bytes) ISO_HIP_TRY(hipMemcpy(dev, table.data(), entry_bytes, hipMemcpyHostToDevice));
-        if (off_bytes) ISO_HIP_TRY(hipMemcpy(dev + entry_bytes, c.can.data(), off_bytes, hipMemcpyHostToDevice));
+        if (off_used) ISO_HIP_TRY(hipMemcpy(dev + entry_bytes, c.can.data(), off_used, hipMemcpyHostToDevice));
         if (pre_bytes)
             ISO_HIP_TRY(hipMemcpy(dev + entry_bytes + off_bytes, prefixes.data(), pre_bytes, hipMemcpyHostToDevice));
     }
@@ -666,6 +797,10 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             pd.l.mesh_shift.entries = dev_entries + pd.first_entry;
             pd.l.mesh_shift.offsets = dev_offsets;
             pd.l.mesh_shift.interior = dev_prefix + pd.first_prefix;
+        } else if (pd.l.kernel == kDeliverKernel) {
+            pd.l.deliver.entries = (const DeliverEntry *)(dev_prefix + pd.first_prefix);
+        } else if (pd.l.kernel == kStagedRoundKernel) {
+            pd.l.staged.entries = dev_entries + pd.first_entry;
         } else if (pd.l.kernel == kBlockKernel) {
             pd.l.block.entries = dev_entries + pd.first_entry;
             pd.l.block.prefix = dev_prefix + pd.first_prefix;

@@ -581,6 +581,182 @@ __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshAr
                       unit_offset_if<V, TAIL>(ch, a.last_offset));
 }
 
+// ---- small blocks re-tiled through LDS (the staged schedule) ----------------------------------
+// A workgroup moves a tile of up to kTileUnits units: the blocks of `ranks` consecutive ranks for
+// all entries of the launch.  It reads them in the order that suits the source (entry after entry
+// of one rank where the source is a rank-major buffer, rank after rank of one plane where it is a
+// slot-major one), eight independent loads per lane, parks them in LDS, and writes them in the
+// order that suits the destination.  Both sides then see runs of hundreds of bytes although the
+// blocks themselves may be 16 bytes.
+constexpr uint32_t kTileUnits = 2048;                  // tiles of 512 to 2048 units measure alike (within 1 %)
+constexpr uint32_t kUnitsPerLane = kTileUnits / kThreads;
+
+struct StagedRoundArgs {
+    const DevEntry *entries;   // the first k_rows entries read a rank-major buffer, the others a slot-major one;
+                               // every destination is a slot-major plane of the workspace
+    TileMap map;
+    uint32_t p, k, k_rows;
+    uint32_t ranks;            // ranks per tile: k * ranks * upb <= kTileUnits
+    uint32_t upb;              // units per block
+    uint32_t inner, pj;        // the moving dimension (1, 1: same-rank copies)
+    FastDiv d_upb, d_row, d_plane, d_inner, d_pj;   // upb; k_rows * upb; ranks * upb
+};
+
+template <typename V, bool NTL, uint32_t UPL>
+__global__ __launch_bounds__(kThreads) void staged_round_kernel(const StagedRoundArgs a) {
+    __shared__ DevEntry lds[kLdsEntries];
+    extern __shared__ __align__(16) unsigned char tile_bytes[];
+    V *tile = (V *)tile_bytes;
+    typedef typename Unaligned<V>::type UV;
+    typedef const UV __attribute__((address_space(1))) *src_ptr;
+    typedef UV __attribute__((address_space(1))) *dst_ptr;
+    const EntryTable<true> table(a.entries, a.k, lds);
+    uint32_t tile_id;
+    if (!tile_of_block(a.map, tile_id)) return;
+    const uint32_t R0 = tile_id * a.ranks;
+    const uint32_t n = a.p - R0 < a.ranks ? a.p - R0 : a.ranks;
+    const uint32_t plane = a.ranks * a.upb, pitch = plane + 1u;      // padded planes: the strided LDS writes spread over the banks
+    const uint32_t n_rows = a.k_rows * plane, n_all = a.k * plane;
+    V regs[UPL];
+    uint32_t at[UPL];                          // where in the tile the unit goes; ~0: no unit
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it) {
+        const uint32_t q = threadIdx.x + it * (uint32_t)kThreads;
+        uint32_t e, r, c, rem;
+        if (q < n_rows) {                                // (rank, entry, unit) over the rank-major sources
+            fast_divmod(q, a.d_row, r, rem);
+            fast_divmod(rem, a.d_upb, e, c);
+        } else {                                         // (entry, rank, unit) over the slot-major sources
+            fast_divmod(q - n_rows, a.d_plane, e, rem);
+            fast_divmod(rem, a.d_upb, r, c);
+            e += a.k_rows;
+        }
+        // a lane with no unit loads the tile's first unit instead and drops it: the eight loads stay
+        // straight-line code, all in flight together
+        const bool has_unit = q < n_all && r < n;
+        e = has_unit ? e : 0u;
+        r = has_unit ? r : 0u;
+        c = has_unit ? c : 0u;
+        const DevEntry en = table[e];
+        const uint32_t R = R0 + r;
+        const uint32_t qq = fast_div(R, a.d_inner);
+        const uint32_t rj = qq - fast_div(qq, a.d_pj) * a.pj;
+        uint32_t srcR = R - en.shift * a.inner;
+        srcR += rj < en.shift ? a.pj * a.inner : 0u;
+        const src_ptr sp = (src_ptr)(block_address(en.src, srcR, en.src_stride) + (uint64_t)c * sizeof(V));
+        if constexpr (NTL && sizeof(V) == 16) regs[it] = __builtin_nontemporal_load(sp);
+        else regs[it] = *sp;
+        at[it] = has_unit ? e * pitch + r * a.upb + c : ~0u;
+    }
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it)
+        if (at[it] != ~0u) tile[at[it]] = regs[it];
+    __syncthreads();
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it) {    // (entry, rank, unit): dense runs of every plane
+        const uint32_t q = threadIdx.x + it * (uint32_t)kThreads;
+        uint32_t e, r, c, rem;
+        fast_divmod(q, a.d_plane, e, rem);
+        fast_divmod(rem, a.d_upb, r, c);
+        if (q < n_all && r < n) {
+            const DevEntry en = table[e];
+            const dst_ptr dp = (dst_ptr)(block_address(en.dst, R0 + r, en.dst_stride) + (uint64_t)c * sizeof(V));
+            if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(tile[e * pitch + rem], dp);
+            else *dp = tile[e * pitch + rem];
+        }
+    }
+}
+
+// Last launch of the staged schedule: entry i brings receive block i of every rank from where its
+// last hop starts (a plane of the workspace or the send buffer), along the entry's own dimension.
+// A workgroup takes `ranks` consecutive ranks: it reads their blocks in the order that suits the
+// sources (as the rounds above do) into an LDS tile, one padded plane per receive block so that
+// the strided LDS accesses spread over the banks, and writes the tile out in row order as one
+// dense run of ranks * s * m bytes: small blocks are written as whole receive rows.
+struct alignas(16) DeliverEntry {
+    uint64_t src;          // address of rank 0's source block
+    uint32_t src_stride;   // bytes between consecutive ranks in the source
+    uint32_t slot;         // receive block i
+    uint32_t shift, pj;    // residue v along the entry's dimension (0: same rank); that dimension's size
+    uint32_t back, wrap;   // v * inner_j; p_j * inner_j
+    FastDiv d_inner, d_pj;
+};
+static_assert(sizeof(DeliverEntry) == 64, "four 16-byte words per entry");
+
+struct DeliverArgs {
+    const DeliverEntry *entries;   // the first k_rows entries read a rank-major buffer
+    uint64_t dst;                  // rank 0's receive row; rows of s blocks, back to back
+    TileMap map;
+    uint32_t p, s, k_rows;
+    uint32_t ranks;                // ranks per workgroup: s * ranks * upb <= UPL * kThreads
+    uint32_t upb;                  // units per block
+    FastDiv d_upb, d_rows, d_plane, d_row;    // upb; k_rows * upb; ranks * upb; s * upb
+};
+
+template <typename V, bool NTL, uint32_t UPL>
+__global__ __launch_bounds__(kThreads) void deliver_kernel(const DeliverArgs a) {
+    __shared__ DeliverEntry lds[kLdsEntries];
+    extern __shared__ __align__(16) unsigned char tile_bytes[];
+    V *tile = (V *)tile_bytes;
+    typedef typename Unaligned<V>::type UV;
+    typedef const UV __attribute__((address_space(1))) *src_ptr;
+    typedef UV __attribute__((address_space(1))) *dst_ptr;
+    for (uint32_t w = threadIdx.x; w < a.s * 4u; w += kThreads) ((vec16_t *)lds)[w] = ((const vec16_t *)a.entries)[w];
+    __syncthreads();
+    uint32_t tile_id;
+    if (!tile_of_block(a.map, tile_id)) return;
+    const uint32_t R0 = tile_id * a.ranks;
+    const uint32_t n = a.p - R0 < a.ranks ? a.p - R0 : a.ranks;
+    const uint32_t plane = a.ranks * a.upb, pitch = plane + 1u;
+    const uint32_t n_rows = a.k_rows * plane, n_all = a.s * plane;
+    V regs[UPL];
+    uint32_t at[UPL];                                    // where in the tile the unit goes; ~0: no unit
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it) {
+        const uint32_t q = threadIdx.x + it * (uint32_t)kThreads;
+        uint32_t e, r, c, rem;
+        if (q < n_rows) {                                // (rank, entry, unit) over the rank-major sources
+            fast_divmod(q, a.d_rows, r, rem);
+            fast_divmod(rem, a.d_upb, e, c);
+        } else {                                         // (entry, rank, unit) over the planes
+            fast_divmod(q - n_rows, a.d_plane, e, rem);
+            fast_divmod(rem, a.d_upb, r, c);
+            e += a.k_rows;
+        }
+        // a lane with no unit loads the tile's first unit instead and drops it
+        const bool has_unit = q < n_all && r < n;
+        e = has_unit ? e : 0u;
+        r = has_unit ? r : 0u;
+        c = has_unit ? c : 0u;
+        const DeliverEntry &en = lds[e];
+        const uint32_t R = R0 + r;
+        const uint32_t qq = fast_div(R, en.d_inner);
+        const uint32_t rj = qq - fast_div(qq, en.d_pj) * en.pj;
+        const uint32_t srcR = R - en.back + (rj < en.shift ? en.wrap : 0u);
+        const src_ptr sp = (src_ptr)(block_address(en.src, srcR, en.src_stride) + (uint64_t)c * sizeof(V));
+        if constexpr (NTL && sizeof(V) == 16) regs[it] = __builtin_nontemporal_load(sp);
+        else regs[it] = *sp;
+        at[it] = has_unit ? en.slot * pitch + r * a.upb + c : ~0u;
+    }
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it)
+        if (at[it] != ~0u) tile[at[it]] = regs[it];
+    __syncthreads();
+    const uint64_t out = a.dst + (uint64_t)R0 * a.s * a.upb * sizeof(V);
+#pragma unroll
+    for (uint32_t it = 0; it < UPL; ++it) {              // (rank, block, unit): the receive rows, back to back
+        const uint32_t q = threadIdx.x + it * (uint32_t)kThreads;
+        uint32_t i, r, c, rem;
+        fast_divmod(q, a.d_row, r, rem);
+        fast_divmod(rem, a.d_upb, i, c);
+        if (r < n) {
+            const dst_ptr dp = (dst_ptr)(out + (uint64_t)q * sizeof(V));
+            if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(tile[i * pitch + r * a.upb + c], dp);
+            else *dp = tile[i * pitch + r * a.upb + c];
+        }
+    }
+}
+
 // Plain streaming copy with the same access shape: the measured ceiling.
 template <typename V>
 __global__ __launch_bounds__(kThreads) void copy_kernel(const V *__restrict__ src, V *__restrict__ dst,

@@ -84,7 +84,7 @@ iso_plan_entry_t mk(int sb, int ss, int db, int ds, int shift, int nb) {
     e.src_buf = sb; e.src_slot = ss; e.dst_buf = db; e.dst_slot = ds;
     e.shift = shift; e.neighbor = nb;
     e.ref = nb;
-    e.reserved = 0;
+    e.dim = -1;
     return e;
 }
 
@@ -528,6 +528,77 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
             else
                 plan_allgather_combined(c, algorithm == ISO_ALG_COMBINED_BYDIM, pl);
             break;
+        case ISO_ALG_COMBINED_STAGED: {
+            // The message-combining schedule, regrouped so that the receive buffer is written only once, by
+            // the last launch, a whole row at a time.  Every move keeps its source, distance and dimension:
+            //  - a move into the receive buffer that is the last one for its block, whose block nobody
+            //    reads afterwards and whose source stays as it is until the end, is taken out of its round
+            //    and put into the last launch (kind DELIVER: every entry moves along its own dimension);
+            //  - any other move into the receive buffer goes to a staging slot of the workspace instead
+            //    (and reads of that block follow it there); if it was the block's last, the last launch
+            //    copies the staging slot into the receive block.
+            // Rounds left without entries disappear.  The workspace is one dense plane per slot, so all
+            // rounds before the last write dense streams whatever the block size is.
+            if (c.mesh) return ISO_ERR_ARG;      // on a mesh untouched receive blocks must keep their content
+            if (op == ISO_OP_ALLTOALL)
+                plan_alltoall_combined(c, false, pl);
+            else
+                plan_allgather_combined(c, false, pl);
+            std::vector<Round> in = std::move(pl.rounds);
+            pl.rounds.clear();
+            const int n_in = (int)in.size();
+            // last round that writes a (buffer, slot); last round that reads receive block i
+            std::vector<int> last_write_recv((size_t)c.s, -1), last_read_recv((size_t)c.s, -1);
+            std::vector<int> last_write_work((size_t)pl.work_slots, -1);
+            for (int ri = 0; ri < n_in; ++ri)
+                for (const iso_plan_entry_t &e : in[(size_t)ri].entries) {
+                    if (e.dst_buf == ISO_BUF_RECV) last_write_recv[(size_t)e.dst_slot] = ri;
+                    if (e.dst_buf == ISO_BUF_WORK) last_write_work[(size_t)e.dst_slot] = ri;
+                    if (e.src_buf == ISO_BUF_RECV) last_read_recv[(size_t)e.src_slot] = ri;
+                }
+            std::vector<int> stage((size_t)c.s, -1);
+            auto stage_of = [&](int i) {
+                if (stage[(size_t)i] < 0) stage[(size_t)i] = pl.work_slots++;
+                return stage[(size_t)i];
+            };
+            Round deliver;
+            deliver.kind = ISO_ROUND_DELIVER;
+            deliver.dim = -1;
+            deliver.entries.resize((size_t)c.s);
+            for (int ri = 0; ri < n_in; ++ri) {
+                Round out;
+                out.kind = in[(size_t)ri].kind;
+                out.dim = in[(size_t)ri].dim;
+                for (iso_plan_entry_t e : in[(size_t)ri].entries) {
+                    const bool source_stays =
+                        e.src_buf == ISO_BUF_SEND ||
+                        (e.src_buf == ISO_BUF_WORK && last_write_work[(size_t)e.src_slot] < ri) ||
+                        (e.src_buf == ISO_BUF_RECV && last_write_recv[(size_t)e.src_slot] < ri);
+                    if (e.src_buf == ISO_BUF_RECV) { e.src_buf = ISO_BUF_WORK; e.src_slot = stage_of(e.src_slot); }
+                    if (e.dst_buf != ISO_BUF_RECV) { out.entries.push_back(e); continue; }
+                    const int i = e.dst_slot;
+                    const bool last_for_block = last_write_recv[(size_t)i] == ri;
+                    if (last_for_block && last_read_recv[(size_t)i] < ri && source_stays) {
+                        e.dim = out.kind == ISO_ROUND_SHIFT ? out.dim : -1;
+                        deliver.entries[(size_t)i] = e;
+                        continue;
+                    }
+                    e.dst_buf = ISO_BUF_WORK;
+                    e.dst_slot = stage_of(i);
+                    out.entries.push_back(e);
+                    if (last_for_block) {
+                        iso_plan_entry_t cp{};
+                        cp.src_buf = ISO_BUF_WORK; cp.src_slot = e.dst_slot;
+                        cp.dst_buf = ISO_BUF_RECV; cp.dst_slot = i;
+                        cp.shift = 0; cp.neighbor = i; cp.ref = i; cp.dim = -1;
+                        deliver.entries[(size_t)i] = cp;
+                    }
+                }
+                if (!out.entries.empty()) pl.rounds.push_back(std::move(out));
+            }
+            if (c.s > 0) pl.rounds.push_back(std::move(deliver));
+            break;
+        }
         case ISO_ALG_ONEHOP: {
             if (c.mesh) return ISO_ERR_ARG;
             // one launch per unit of coordinate: refuse neighbourhoods whose raw coordinates
@@ -556,6 +627,9 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
         default:
             return ISO_ERR_ARG;
     }
+    for (Round &r : pl.rounds)
+        if (r.kind != ISO_ROUND_DELIVER)
+            for (iso_plan_entry_t &e : r.entries) e.dim = r.kind == ISO_ROUND_SHIFT ? r.dim : -1;
     out = std::move(pl);
     return ISO_SUCCESS;
 }

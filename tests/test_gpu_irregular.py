@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
 ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
-        iso.ISO_ALG_ONEHOP]
-ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop"}
+        iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop", 5: "combined_staged"}
 RNG = np.random.default_rng(77)
 
 CASES = [

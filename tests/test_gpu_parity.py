@@ -17,8 +17,8 @@ pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
 ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
-        iso.ISO_ALG_ONEHOP]
-ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop"}
+        iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED]
+ALG_NAMES = {0: "combined", 1: "combined_bydim", 2: "sx_rounds", 3: "sx_fused", 4: "onehop", 5: "combined_staged"}
 
 SMALL = [
     ((5,), [(1,), (-2,), (7,)]),
@@ -106,6 +106,12 @@ def test_shales_neighbourhood(dims, alg):
     # one-hop schedule (Section 3.1): per dimension the longest walk up plus the longest walk down,
     # counted on the coordinates as given
     onehop_rounds = sum(max(c[j] for c in offsets) - min(c[j] for c in offsets) for j in range(3))
+    # staged schedule: the rounds that keep an entry, then (more than 128 neighbours: no kernel of
+    # its own for the last launch) one launch per dimension that some block's last hop runs along
+    comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32))
+    plan = iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED_STAGED)
+    n_rounds = iso.iso_plan_info(plan)["launches"]
+    staged_launches = n_rounds - 1 + len({e["dim"] for e in iso.iso_plan_entries(plan, n_rounds - 1)})
     for m in (16, 40):
         send_h = gen.alltoall_send(77, p, s, m)
         send = torch.from_numpy(send_h).to(DEV)
@@ -113,7 +119,8 @@ def test_shales_neighbourhood(dims, alg):
         assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h)), f"alltoall m={m}"
         assert info["launches"] == {iso.ISO_ALG_COMBINED: direct_rounds, iso.ISO_ALG_COMBINED_BYDIM: 3,
                                     iso.ISO_ALG_SX_ROUNDS: s, iso.ISO_ALG_SX_FUSED: 1,
-                                    iso.ISO_ALG_ONEHOP: onehop_rounds}[alg]
+                                    iso.ISO_ALG_ONEHOP: onehop_rounds,
+                                    iso.ISO_ALG_COMBINED_STAGED: staged_launches}[alg]
         del send, recv
         send_h = gen.allgather_send(78, p, m)
         send = torch.from_numpy(send_h).to(DEV)
@@ -122,7 +129,8 @@ def test_shales_neighbourhood(dims, alg):
     assert direct_rounds == (42 if dims[0] == 15 else 22) and onehop_rounds == 42
 
 
-@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_SX_FUSED], ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_SX_FUSED, iso.ISO_ALG_COMBINED_STAGED],
+                         ids=lambda a: ALG_NAMES[a])
 @pytest.mark.parametrize("send_off,recv_off", [(0, 0), (8, 8), (8, 0), (4, 12), (2, 2), (1, 1), (1, 2), (3, 0),
                                                (0, 13)])
 def test_unaligned_buffers_keep_the_full_unit_width(send_off, recv_off, alg):
@@ -182,7 +190,7 @@ def test_restart_and_side_stream_give_the_same_result():
         assert np.array_equal(recv.cpu().numpy(), want)
         assert info["launches"] == {iso.ISO_ALG_COMBINED: 4, iso.ISO_ALG_COMBINED_BYDIM: 2,
                                     iso.ISO_ALG_SX_ROUNDS: 8, iso.ISO_ALG_SX_FUSED: 1,
-                                    iso.ISO_ALG_ONEHOP: 4}[alg]
+                                    iso.ISO_ALG_ONEHOP: 4, iso.ISO_ALG_COMBINED_STAGED: 3}[alg]
 
 
 @pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS],
@@ -344,6 +352,10 @@ def test_named_workloads_full_size(key, alg):
                 moves = (orc.direct_alltoall_volume(cfg.dims, cfg.offsets) if op == iso.ISO_OP_ALLTOALL
                          else orc.direct_allgather_volume(cfg.dims, cfg.offsets))
                 assert info["bytes_read"] == moves * cfg.p * m == info["bytes_written"]
+            if alg == iso.ISO_ALG_COMBINED_STAGED and op == iso.ISO_OP_ALLTOALL:
+                # the combined schedule's moves, regrouped: not a byte more
+                assert info["bytes_read"] == orc.direct_alltoall_volume(cfg.dims, cfg.offsets) * cfg.p * m
+                assert info["launches"] < len(orc.direct_rounds(cfg.dims, cfg.offsets)) or cfg.d == 1
             if alg == iso.ISO_ALG_ONEHOP:
                 assert info["launches"] == orc.onehop_rounds(cfg.offsets)
                 if op == iso.ISO_OP_ALLTOALL:

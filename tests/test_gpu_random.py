@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
 TORUS_ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
-              iso.ISO_ALG_ONEHOP]
+              iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED]
 MESH_ALGS = TORUS_ALGS[:4]
 
 

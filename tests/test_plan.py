@@ -32,7 +32,7 @@ CASES = [
     ((3, 3), []),                                                         # empty neighbourhood
 ]
 ALGS = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_ROUNDS, iso.ISO_ALG_SX_FUSED,
-        iso.ISO_ALG_ONEHOP]
+        iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED]
 
 
 def test_library_exports_every_declared_symbol():
@@ -123,8 +123,13 @@ def _replay(dims, offsets, op, rounds, work_slots, send, m):
                 data = np.roll(src, e["shift"], axis=info["dim"])
             elif info["kind"] == iso.ISO_ROUND_SELF:
                 data = src.copy()
+            elif info["kind"] == iso.ISO_ROUND_DELIVER:       # every entry along its own dimension
+                assert -1 <= e["dim"] < d and (e["dim"] >= 0 or e["shift"] == 0)
+                data = np.roll(src, e["shift"], axis=e["dim"]) if e["dim"] >= 0 else src.copy()
             else:
                 data = np.roll(src, tuple(offsets[e["neighbor"]]), axis=tuple(range(d)))
+            if info["kind"] != iso.ISO_ROUND_DELIVER:
+                assert e["dim"] == info["dim"]
             staged.append((e, data))
             reads.add((e["src_buf"], e["src_slot"]))
             assert (e["dst_buf"], e["dst_slot"]) not in writes, "two entries write one block"
@@ -139,6 +144,33 @@ def _replay(dims, offsets, op, rounds, work_slots, send, m):
             bufs[e["dst_buf"]][..., e["dst_slot"], :] = data
             written.add((e["dst_buf"], e["dst_slot"]))
     return bufs[iso.ISO_BUF_RECV].reshape(p, max(s, 1), m)[:, :s], written
+
+
+def _check_staged_shape(op, dims, offsets, rounds):
+    """Staged schedule: the receive buffer is written by the last launch only, block i by entry i, and
+    every move of the rounds before is a move of the combined schedule's round of the same dimension
+    and distance."""
+    s = len(offsets)
+    if not s:
+        assert not rounds
+        return
+    for info, entries in rounds[:-1]:
+        assert entries and info["kind"] in (iso.ISO_ROUND_SHIFT, iso.ISO_ROUND_SELF)
+        assert all(e["dst_buf"] == iso.ISO_BUF_WORK and e["src_buf"] != iso.ISO_BUF_RECV for e in entries)
+    info, entries = rounds[-1]
+    assert info["kind"] == iso.ISO_ROUND_DELIVER and info["dim"] == -1
+    assert [(e["dst_buf"], e["dst_slot"]) for e in entries] == [(iso.ISO_BUF_RECV, i) for i in range(s)]
+    assert all(e["src_buf"] != iso.ISO_BUF_RECV for e in entries)
+    legal = set(orc.direct_rounds(dims, offsets))
+    shift_rounds = [(i, es) for i, es in rounds[:-1] if i["kind"] == iso.ISO_ROUND_SHIFT]
+    seen = [(i["dim"], es[0]["shift"]) for i, es in shift_rounds]
+    want = [r for r in orc.direct_rounds(dims, offsets) if r in seen]
+    if op == iso.ISO_OP_ALLTOALL:
+        assert seen == want                     # a subsequence of the rounds, in their order
+        for i, es in shift_rounds:
+            assert len({e["shift"] for e in es}) == 1
+    for e in entries:
+        assert e["dim"] < 0 or (e["dim"], e["shift"]) in legal
 
 
 @pytest.mark.parametrize("alg", ALGS)
@@ -169,6 +201,13 @@ def test_alltoall_plan_reaches_the_oracle_result(dims, offsets, alg):
         else:
             assert len(shift_rounds) == len({j for j, _ in orc.direct_rounds(dims, offsets)})
         assert len(rounds) - len(shift_rounds) == (1 if n_self else 0)
+    elif alg == iso.ISO_ALG_COMBINED_STAGED:
+        # the moves of the combined schedule, each block's last hop in the last launch; a block with three
+        # or more hops passes through the receive buffer on its way in that schedule: an extra slot here
+        assert pinfo["entries"] == orc.direct_alltoall_volume(dims, offsets) + n_self
+        hops = [sum(1 for c in C if c) for C in can]
+        assert pinfo["work_slots"] == sum(1 for h in hops if h >= 2) + sum(1 for h in hops if h >= 3)
+        _check_staged_shape(iso.ISO_OP_ALLTOALL, dims, offsets, rounds)
     elif alg == iso.ISO_ALG_ONEHOP:
         # Proposition 1: D steps of one hop each, V = sum of 1-norms block-moves (raw coordinates)
         raw_self = sum(1 for C in offsets if not any(C))
@@ -207,6 +246,13 @@ def test_allgather_plan_reaches_the_oracle_result(dims, offsets, alg):
         if alg == iso.ISO_ALG_COMBINED:
             n_shift = sum(1 for r in rounds if r[0]["kind"] == iso.ISO_ROUND_SHIFT)
             assert n_shift == len(orc.direct_rounds(dims, offsets))
+    elif alg == iso.ISO_ALG_COMBINED_STAGED:
+        # the trie's moves, plus one copy for every block that had to be complete before the last launch
+        n_self = sum(1 for C in orc.canonical(dims, offsets) if not any(C))
+        moves = iso.iso_neighborhood_info(comm)["allgather_moves"]
+        copies = sum(1 for e in rounds[-1][1] if e["dim"] < 0) - n_self if s else 0
+        assert 0 <= copies <= s and pinfo["entries"] == moves + n_self + copies
+        _check_staged_shape(iso.ISO_OP_ALLGATHER, dims, offsets, rounds)
     elif alg == iso.ISO_ALG_ONEHOP:
         # Proposition 2: the same D steps, W block-moves (plus one per repeated offset)
         order = pinfo["dim_order"][:len(dims)]
