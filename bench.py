@@ -374,8 +374,12 @@ class Bench:
         avg_launch_ms = ms_per_step / self.launches
         achieved = alg_bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
         kernel = ("vector_round_kernel" if args.algorithm.startswith("sx") else
+                  "deliver_kernel" if args.algorithm == "staged" and m % 16 == 0 and s * (m // 16) <= 2048 and s <= 128
+                  and not (args.irregular or args.mesh or args.pad or self.slot) else
                   "block_round_kernel" if args.irregular else
-                  "mesh_shift_round_kernel" if args.mesh else "shift_round_kernel") + "<16B>"
+                  "mesh_shift_round_kernel" if args.mesh else
+                  "shift_round_uniform_kernel" if m % 1024 == 0 and (self.slot or m <= 2048) else
+                  "shift_round_kernel") + "<16B>"
         tag = self.tag()
         roofline = {
             "kernel": kernel, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
