@@ -257,12 +257,14 @@ class Bench:
                     at += -(-p * sz // 16) * 16
                 send = torch.empty(at, dtype=torch.uint8, device=dev).fill_(3)
                 recv = torch.empty(at, dtype=torch.uint8, device=dev)
+                torch.cuda.synchronize()
                 t = time.perf_counter()
                 req = iso.iso_neighbor_alltoallv_init_layout(send, sizes, pd, 0, recv, sizes, pd, 0,
                                                              iso.ISO_LAYOUT_SLOT_MAJOR, work, self.comm, alg)
             else:
                 send = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
                 recv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
+                torch.cuda.synchronize()
                 t = time.perf_counter()
                 req = iso.iso_neighbor_alltoallv_init(send, sizes, displs, ext, recv, sizes, displs, ext,
                                                       work, self.comm, alg)
@@ -279,6 +281,7 @@ class Bench:
         init = iso.iso_neighbor_alltoall_init_layout if op == iso.ISO_OP_ALLTOALL else \
             iso.iso_neighbor_allgather_init_layout
         layout = iso.ISO_LAYOUT_SLOT_MAJOR if (timed_buffers and self.slot) else iso.ISO_LAYOUT_RANK_MAJOR
+        torch.cuda.synchronize()                 # the init call copies its table synchronously: keep the fills out of its time
         t = time.perf_counter()
         req = init(send, recv, m, layout, work, self.comm, alg)
         dt = (time.perf_counter() - t) * 1e3

@@ -675,68 +675,41 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 }
                 for (uint32_t q = 0; q < k; ++q) table.push_back(ents[done + q].de);
             } else {
-                // irregular blocks, or a mesh: as many entries as fit the 32-bit unit index (each of the
-                // at most kBlockSegments segments is padded to whole tiles)
+                // irregular blocks, or a mesh: as many entries as fit the 32-bit unit index
                 l.kernel = kBlockKernel;
                 l.mesh = c.mesh;
                 l.block.shift_dim = r.kind == ISO_ROUND_SHIFT ? r.dim : -1;
                 for (int j = 0; j < c.d; ++j)
                     if (c.periodic[(size_t)j]) l.block.periodic_mask |= 1u << j;
+                // per launch: k + 1 prefix values, then k multipliers of the divisions by the entries'
+                // unit counts (entry-major order only; the two shifts go into the entry's meta word)
                 const bool entry_major = lay.slot_major;
                 const uint64_t scale = entry_major ? p : 1;    // prefix counts all ranks' units, or one row's
                 uint64_t row_units = 0;
+                prefixes.push_back(0);
                 while (done + k < ents.size()) {
                     const uint64_t next = row_units + ents[done + k].de.units;
-                    if (next * p + kBlockSegments * kThreads > kMaxUnits) break;
+                    if (next * p > kMaxUnits) break;
                     row_units = next;
-                    ++k;
-                }
-                if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
-                // one segment per unit width, narrowest first; inside a segment the entries keep their order.
-                // Per segment: k_c + 1 prefix values, then k_c multipliers of the divisions by the entries'
-                // unit counts (entry-major order only; the two shifts go into the entry's meta word)
-                BlockArgs &b = l.block;
-                std::vector<size_t> order;                     // the launch's entries, segment by segment
-                uint32_t tiles = 0, nseg = 0;
-                for (int l2 = 0; l2 <= 4; ++l2) {
-                    std::vector<size_t> members;
-                    for (uint32_t q = 0; q < k; ++q)
-                        if ((ents[done + q].de.meta & 0xFFu) == (uint32_t)l2) members.push_back(done + q);
-                    if (members.empty()) continue;
-                    BlockSegment &sg = b.seg[nseg++];
-                    sg.first_tile = tiles;
-                    sg.first_entry = (uint32_t)order.size();
-                    sg.first_prefix = (uint32_t)(prefixes.size() - pd.first_prefix);
-                    sg.k = (uint32_t)members.size();
-                    sg.width_log2 = (uint32_t)l2;
-                    uint64_t seg_row = 0;
-                    prefixes.push_back(0);
-                    sg.equal_units = ents[members[0]].de.units;
-                    for (size_t mi : members) {
-                        DevEntry de = ents[mi].de;
-                        if (de.units != sg.equal_units) sg.equal_units = 0;
-                        seg_row += de.units;
-                        prefixes.push_back((uint32_t)(seg_row * scale));
-                        order.push_back(mi);
-                    }
-                    for (size_t mi : members) prefixes.push_back(make_fastdiv(ents[mi].de.units).mul);
-                    sg.total = (uint32_t)(seg_row * p);
-                    sg.d_row = make_fastdiv((uint32_t)seg_row);
-                    sg.d_units = make_fastdiv(sg.equal_units ? sg.equal_units : 1u);
-                    sg.d_plane = make_fastdiv(sg.equal_units ? (uint32_t)(p * sg.equal_units) : 1u);
-                    tiles += (uint32_t)(((uint64_t)sg.total + kThreads - 1) / kThreads);
-                }
-                for (size_t mi : order) {
-                    DevEntry de = ents[mi].de;
+                    DevEntry de = ents[done + k].de;
                     const FastDiv by_units = make_fastdiv(de.units);
                     de.meta |= (by_units.sh1 << 24) | (by_units.sh2 << 25);
                     table.push_back(de);
+                    prefixes.push_back((uint32_t)(row_units * scale));
+                    ++k;
                 }
-                total = (uint64_t)tiles * kThreads;
-                b.n_segments = nseg;
-                b.n_prefix = (uint32_t)(prefixes.size() - pd.first_prefix);
+                if (k == 0) return ISO_ERR_TOO_LARGE;          // one block plane alone is too large
+                for (uint32_t q = 0; q < k; ++q) prefixes.push_back(make_fastdiv(ents[done + q].de.units).mul);
+                total = row_units * p;
+                BlockArgs &b = l.block;
                 b.entry_major = entry_major;
+                b.equal_units = ents[done].de.units;
+                for (uint32_t q = 1; q < k; ++q)
+                    if (ents[done + q].de.units != b.equal_units) b.equal_units = 0;
+                b.d_units = make_fastdiv(b.equal_units ? b.equal_units : 1u);
+                b.d_plane = make_fastdiv(b.equal_units ? (uint32_t)(p * b.equal_units) : 1u);
                 b.vector_round = r.kind == ISO_ROUND_VECTOR;
+                b.d_row = make_fastdiv((uint32_t)row_units);
                 const bool shift = r.kind == ISO_ROUND_SHIFT;
                 b.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
                 b.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;
@@ -753,7 +726,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
             l.stream_loads = op == ISO_OP_ALLTOALL && r.kind != ISO_ROUND_VECTOR &&
                              (l.kernel == kShiftKernel || l.kernel == kMeshShiftKernel || l.kernel == kStagedRoundKernel ||
                               l.kernel == kDeliverKernel ||
-                              (l.kernel == kBlockKernel && l.block.n_segments == 1 && l.block.seg[0].equal_units));
+                              (l.kernel == kBlockKernel && l.block.equal_units));
             std::vector<Side> src_sides, dst_sides;
             for (uint32_t q = 0; q < k; ++q) {
                 const HostEntry &he = ents[done + q];

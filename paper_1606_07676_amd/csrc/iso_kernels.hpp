@@ -315,58 +315,42 @@ __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs
 // Irregular blocks (the v/w interfaces of Section 2): every entry has its own
 // block size and its own unit width (16 bytes for blocks of at least 16 bytes,
 // narrower below, e.g. a 1-byte corner block next to a 16 KiB face block).
-// A launch is cut into segments, one per unit width that occurs, narrowest first,
-// each padded to whole tiles, so that a workgroup (hence every wavefront) moves
-// units of ONE width and the choice of the access width is a uniform branch.
-// (What tiny blocks cost is not in the kernel: a block of a few bytes in every
-// rank's row costs a memory row activation per block on each side, whatever
-// moves it.  On the stencil-shaped all-to-all of Section 4, 4096 / 64 / 1 byte
-// blocks, the 6 % of bytes in the small blocks take a quarter of the time, and a
-// fifth of the fused s-exchange's.)  Inside a segment a rank's
-// units are the concatenation of the units of the segment's entries; `prefix[e]`
-// is the first unit of entry e.  The flat index is split into (rank, unit in
-// row), the entry is found by division when the segment's blocks are equal,
-// else by binary search in the prefix array.  On slot-major buffers (one plane
-// of p blocks per neighbour) the order is (entry, rank, unit) instead: prefix[e]
-// then counts the units of all ranks in the entries before e, and the position
-// inside the plane is divided by the entry's own unit count.
+// A rank's units are the concatenation of its entries' units; `prefix[e]` is
+// the first unit of entry e.  The flat index is split into (rank, unit in row),
+// the entry is found by binary search in the prefix array.  On slot-major
+// buffers (one plane of p blocks per neighbour) the order is (entry, rank, unit)
+// instead: prefix[e] then counts the units of all ranks in the entries before e,
+// and the position inside the plane is divided by the entry's own unit count.
+// (Measured against this form and dropped: the launch cut into one segment per unit
+// width, each a whole number of tiles, so that the width switch is uniform in a
+// workgroup.  Selecting the segment's constants puts one more stage of dependent
+// scalar loads in front of every wavefront's load: stencil-shaped all-to-all,
+// 4096 / 64 / 1 byte blocks, -2 % on rank-major buffers, -15 % on slot-major ones,
+// -11 % for the fused s-exchange.  What tiny blocks cost is not in the kernel: a
+// block of a few bytes in every rank's row is a memory access of its own on each
+// side, whatever moves it.)
 //
 // MESH (Section 7, non-periodic dimensions): coordinates of non-periodic
 // dimensions are signed and nothing wraps there.  A move happens at rank R only
 // if R - C^ref stays inside the mesh in every dimension of the entry's mask
 // (the non-periodic dimensions routed up to and including this round in which
 // C^ref is non-zero); otherwise the destination keeps its content.
-struct BlockSegment {
-    uint32_t first_tile;       // tiles of the segments are consecutive
-    uint32_t first_entry;      // of this segment in the launch's entry table
-    uint32_t first_prefix;     // of this segment's [k + 1] prefix values and [k] multipliers in the prefix array
-    uint32_t k;                // entries
-    uint32_t total;            // units of this segment = p * units of a row
-    uint32_t width_log2;       // log2 of the unit width in bytes
-    uint32_t equal_units;      // != 0: every entry of the segment has this many units (no search)
-    uint32_t reserved;
-    FastDiv d_row, d_units, d_plane;   // units of a row; equal_units; p * equal_units
-};
-constexpr uint32_t kBlockSegments = 5;    // unit widths 16, 8, 4, 2, 1
-
 struct BlockArgs {
     const DevEntry *entries;
-    const uint32_t *prefix;
+    const uint32_t *prefix;    // [k + 1] first unit of every entry, then [k] multipliers (entry-major order)
     const uint32_t *offsets;   // [s][d] effective coordinates (residues; signed where non-periodic)
     TileMap map;
-    uint32_t total;            // tiles * 256
-    uint32_t k;                // entries of all segments
-    uint32_t n_prefix;         // words of all segments' prefix arrays
-    uint32_t n_segments;
+    uint32_t total;            // p * row_units
+    uint32_t k;
     uint32_t vector_round;     // 0: shift along one dimension, 1: full offset vector
     uint32_t inner, pj;        // shift rounds
     int32_t shift_dim;         // shift rounds: the dimension (-1: same-rank copy)
     uint32_t periodic_mask;    // bit j set: dimension j wraps
     int32_t d;
+    uint32_t equal_units;      // != 0: every entry of the launch has this many units (no search)
     uint32_t entry_major;      // slot-major buffers: units ordered (entry, rank, unit) and prefix[e] counts
                                // the units of all ranks before entry e; else (rank, entry, unit)
-    FastDiv d_inner, d_pj;
-    BlockSegment seg[kBlockSegments];
+    FastDiv d_row, d_inner, d_pj, d_units, d_plane;   // d_plane: p * equal_units
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
@@ -454,38 +438,27 @@ __device__ __forceinline__ bool mesh_source_rank(const Args &a, const DevEntry &
 template <bool LDS, bool MESH, bool NTL>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
-    __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + kBlockSegments : 1];
+    __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
     const uint32_t *prefix = a.prefix;
     if constexpr (LDS) {
-        for (uint32_t q = threadIdx.x; q < a.n_prefix; q += kThreads) lds_prefix[q] = a.prefix[q];
+        for (uint32_t q = threadIdx.x; q <= 2 * a.k; q += kThreads) lds_prefix[q] = a.prefix[q];
         prefix = lds_prefix;
     }
     const EntryTable<LDS> table(a.entries, a.k, lds);     // synchronises the workgroup when LDS
     uint32_t tile;
     if (!tile_of_block(a.map, tile)) return;
-    // The segment of this tile (uniform in the workgroup), chosen as a pointer into the argument
-    // struct with compile-time indices: the struct is then still read straight from the kernel
-    // argument segment with scalar loads.  (Everything below exists once per kernel on purpose: the
-    // compiler gives up that direct reading, and has every lane copy the 800-byte struct to private
-    // memory first, once the struct is read at more than a few hundred places.)
-    const BlockSegment *sp = &a.seg[0];
-#pragma unroll
-    for (uint32_t q = 1; q < kBlockSegments; ++q)
-        if (q < a.n_segments && tile >= a.seg[q].first_tile) sp = &a.seg[q];
-    const BlockSegment &sg = *sp;
-    const uint32_t u = (tile - sg.first_tile) * (uint32_t)kThreads + threadIdx.x;
-    if (u >= sg.total) return;
-    prefix += sg.first_prefix;
-    // flat index -> rank R, entry lo of the segment, unit ch of that entry's block
+    const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
+    if (u >= a.total) return;
+    // flat index -> rank R, entry lo, unit ch of that entry's block
     uint32_t R = 0, lo = 0, ch = 0, w = u;
-    if (!a.entry_major) fast_divmod(u, sg.d_row, R, w);   // w: unit inside the rank's row
+    if (!a.entry_major) fast_divmod(u, a.d_row, R, w);    // w: unit inside the rank's row
     // entry-major: w counts through the entries one after another, each with the units of all p ranks
-    if (sg.k == 1) {
+    if (a.k == 1) {
         ch = w;
-    } else if (sg.equal_units) {                           // equal blocks: plain division, no search
-        fast_divmod(w, a.entry_major ? sg.d_plane : sg.d_units, lo, ch);
+    } else if (a.equal_units) {                            // equal blocks: plain division, no search
+        fast_divmod(w, a.entry_major ? a.d_plane : a.d_units, lo, ch);
     } else {
-        uint32_t hi = sg.k;                                // largest e with prefix[e] <= w
+        uint32_t hi = a.k;                                 // largest e with prefix[e] <= w
         while (hi - lo > 1) {
             const uint32_t mid = (lo + hi) >> 1;
             if (prefix[mid] <= w) lo = mid;
@@ -493,11 +466,11 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
         }
         ch = w - prefix[lo];
     }
-    const DevEntry en = table[sg.first_entry + lo];
+    const DevEntry en = table[lo];
     if (a.entry_major) {                                   // ch still counts (rank, unit) inside the plane
-        const FastDiv by_units = sg.equal_units
-                                     ? sg.d_units
-                                     : FastDiv{prefix[sg.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
+        const FastDiv by_units = a.equal_units
+                                     ? a.d_units
+                                     : FastDiv{prefix[a.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
         const uint32_t in_plane = ch;
         fast_divmod(in_plane, by_units, R, ch);
     }
@@ -514,7 +487,7 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     }
     const uint64_t src = block_address(en.src, srcR, en.src_stride);
     const uint64_t dst = block_address(en.dst, R, en.dst_stride);
-    switch (sg.width_log2) {                               // uniform: one path per workgroup
+    switch (en.meta & 0xFFu) {
         case 4: move_unit<vec16_t, NTL>(dst, src, unit_offset<vec16_t>(ch, en.last_offset)); break;
         case 3: move_unit<vec8_t, false>(dst, src, unit_offset<vec8_t>(ch, en.last_offset)); break;
         case 2: move_unit<uint32_t, false>(dst, src, unit_offset<uint32_t>(ch, en.last_offset)); break;
