@@ -509,7 +509,7 @@ class Bench:
                 isend = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
                 irecv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
                 for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
-                                  ("sx_fused", iso.ISO_ALG_SX_FUSED)):
+                                  ("combined_staged", iso.ISO_ALG_COMBINED_STAGED), ("sx_fused", iso.ISO_ALG_SX_FUSED)):
                     wsb = iso.iso_workspace_bytes_v(icomm, iso.ISO_OP_ALLTOALL, alg, sizes)
                     iwork = torch.empty(max(wsb, 16), dtype=torch.uint8, device=dev)
                     r = iso.iso_neighbor_alltoallv_init(isend, sizes, displs, ext, irecv, sizes, displs, ext,

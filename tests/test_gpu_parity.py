@@ -421,3 +421,23 @@ def test_sx_init_calls_are_the_straightforward_algorithm(mode):
     with pytest.raises(iso.IsoError) as e:
         iso.iso_neighbor_alltoall_sx_init(send, recv, m, 7, comm)
     assert e.value.status == iso.ISO_ERR_ARG
+
+
+@pytest.mark.parametrize("s,m", [(128, 256), (128, 16), (127, 256), (129, 16), (26, 1264), (26, 1248), (5, 6560), (1, 32768),
+                                 (1, 32784)])
+def test_staged_schedule_at_the_limits_of_its_tiles(s, m):
+    """The staged schedule's own kernels take up to 128 neighbours and rows of up to 2048 units of 16 bytes
+    (one tile); one more neighbour or unit and the same plan runs on the general kernels.  Both sides of
+    both limits, on a torus whose rank count (105) is no multiple of any tile's rank count, against the
+    oracle, every byte; and a single process."""
+    for dims in ((7, 5, 3), (1, 1, 1)):
+        p = int(np.prod(dims))
+        offsets = gen.random_distinct(3, -3, 3, min(s, 300), 7 + s)[:s] if s > 1 else [(1, 2, 0)]
+        while len(offsets) < s:                           # fewer distinct vectors than asked for: repeat some
+            offsets = offsets + offsets[:s - len(offsets)]
+        send_h = gen.alltoall_send(11, p, s, m)
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED_STAGED, m, torch.from_numpy(send_h).to(DEV))
+        assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h)), (dims, s, m)
+        one_h = gen.allgather_send(12, p, m)
+        recv, info = _run(dims, offsets, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED_STAGED, m, torch.from_numpy(one_h).to(DEV))
+        assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, one_h)), (dims, s, m)

@@ -81,3 +81,35 @@ def test_u8_blocks_are_one_draw_per_byte():
     counts = np.bincount(b.reshape(-1), minlength=256)
     assert counts.min() > 0.7 * b.size / 256 and counts.max() < 1.3 * b.size / 256
     assert gen.get_config(5).kind == "u8"
+
+
+def test_recorded_traffic_summaries_cover_the_benchmark_workloads():
+    """bench.py cannot read hardware counters from inside the process: roofline.traffic is the value
+    of the committed rocprofv3 summary of the same workload.  Every workload of the default run has
+    one, its figures are consistent, and every summary states the command that made it."""
+    import glob
+    import os
+    import re
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    for tag in ("c5_m4096", "c2_m256", "c3_m1024", "c4_m128"):
+        t = bench.recorded_traffic(tag)
+        assert isinstance(t, int) and t > 0, tag
+    files = sorted(glob.glob(os.path.join(root, "profiles", "*.txt")))
+    assert len(files) >= 20
+    for path in files:
+        text = open(path).read()
+        assert "rocprofv3 --" in text and "python3 bench.py" in text, path
+        assert "_work" not in text, path
+        if path.endswith("_hbm_traffic.txt"):
+            t = int(re.search(r"^traffic_bytes_per_launch = (\d+)", text, re.M).group(1))
+            a = int(re.search(r"^algorithmic_bytes_per_launch = (\d+)", text, re.M).group(1))
+            assert 0.5 < t / a < 3.0, path
+    # the benchmark workloads move what the schedule asks for and nothing more
+    for tag in ("c5_m4096", "c2_m256", "c3_m1024", "c4_m128"):
+        (path,) = glob.glob(os.path.join(root, "profiles", f"*{tag}_hbm_traffic.txt"))
+        text = open(path).read()
+        a = int(re.search(r"^algorithmic_bytes_per_launch = (\d+)", text, re.M).group(1))
+        assert abs(bench.recorded_traffic(tag) / a - 1.0) < 0.01, tag
