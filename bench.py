@@ -98,7 +98,7 @@ def small_sweep():
     dev = "cuda:0"
     stream = torch.cuda.current_stream()
     algs = (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
-            ("onehop", iso.ISO_ALG_ONEHOP), ("sx_rounds", iso.ISO_ALG_SX_ROUNDS), ("sx_fused", iso.ISO_ALG_SX_FUSED))
+            ("combined_staged", iso.ISO_ALG_COMBINED_STAGED), ("onehop", iso.ISO_ALG_ONEHOP), ("sx_rounds", iso.ISO_ALG_SX_ROUNDS), ("sx_fused", iso.ISO_ALG_SX_FUSED))
     cases = (("moore_d2_r1", (30, 16), gen.moore(2, 1)), ("moore_d3_r1", (8, 8, 8), gen.moore(3, 1)),
              ("moore_d4_r1", (6, 5, 4, 4), gen.moore(4, 1)), ("moore_d5_r1", (4,) * 5, gen.moore(5, 1)),
              ("moore_d3_r3", (8, 8, 8), gen.moore(3, 3)), ("shales_d3_r3_r7", (9, 8, 8), gen.shales(3, (3, 7))))

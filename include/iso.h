@@ -77,7 +77,8 @@ enum iso_algorithm {
      * paper's [p][s][m] layout, where a round that writes a few blocks of every
      * rank's row costs far more memory traffic than the blocks hold.  The moves are
      * those of ISO_ALG_COMBINED (same sources, distances and dimensions, same
-     * sum_i nnz(C^i) count for the all-to-all), but the receive buffer is written
+     * sum_i nnz(C^i) count for the all-to-all), the rounds of a dimension issued as
+     * one launch as in ISO_ALG_COMBINED_BYDIM, but the receive buffer is written
      * by the last launch only: the last hop of every block is taken out of its round
      * and all of them run as one launch (ISO_ROUND_DELIVER) that gathers, through
      * LDS, every rank's s blocks and writes whole receive rows.  A move into the

@@ -540,10 +540,12 @@ int build_plan(const Comm &c, int op, int algorithm, Plan &out) {
             // Rounds left without entries disappear.  The workspace is one dense plane per slot, so all
             // rounds before the last write dense streams whatever the block size is.
             if (c.mesh) return ISO_ERR_ARG;      // on a mesh untouched receive blocks must keep their content
+            // (built on the rounds of a dimension taken together, as ISO_ALG_COMBINED_BYDIM does: the pieces that
+            // the + and - rounds of a dimension read from a send-buffer row share memory lines; 5 % at 16 bytes)
             if (op == ISO_OP_ALLTOALL)
-                plan_alltoall_combined(c, false, pl);
+                plan_alltoall_combined(c, true, pl);
             else
-                plan_allgather_combined(c, false, pl);
+                plan_allgather_combined(c, true, pl);
             std::vector<Round> in = std::move(pl.rounds);
             pl.rounds.clear();
             const int n_in = (int)in.size();

@@ -190,7 +190,7 @@ def test_restart_and_side_stream_give_the_same_result():
         assert np.array_equal(recv.cpu().numpy(), want)
         assert info["launches"] == {iso.ISO_ALG_COMBINED: 4, iso.ISO_ALG_COMBINED_BYDIM: 2,
                                     iso.ISO_ALG_SX_ROUNDS: 8, iso.ISO_ALG_SX_FUSED: 1,
-                                    iso.ISO_ALG_ONEHOP: 4, iso.ISO_ALG_COMBINED_STAGED: 3}[alg]
+                                    iso.ISO_ALG_ONEHOP: 4, iso.ISO_ALG_COMBINED_STAGED: 2}[alg]
 
 
 @pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS],

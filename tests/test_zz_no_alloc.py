@@ -37,7 +37,7 @@ def _persistent(comm, send, p, s, m, alg):
 
 
 @pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_FUSED,
-                                 iso.ISO_ALG_ONEHOP])
+                                 iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED])
 def test_noalloc_equals_persistent_calls_in_a_row(alg):
     prepared = []
     for q, (dims, offsets, m) in enumerate(CASES):
@@ -52,11 +52,24 @@ def test_noalloc_equals_persistent_calls_in_a_row(alg):
     # the calls back to back on one stream, no synchronisation in between: each call's table
     # and intermediate blocks overwrite the previous call's in the shared array
     before = torch.cuda.memory_allocated()
-    for dims, offsets, m, comm, send_h, send, want, recv in prepared:
+    limit = iso.ISO_NOALLOC_SCRATCH_BYTES - iso.ISO_NOALLOC_TABLE_BYTES
+    refused = set()
+    for q, (dims, offsets, m, comm, send_h, send, want, recv) in enumerate(prepared):
+        if iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, alg, m) > limit:
+            # (the staged schedule keeps 28 blocks per rank in the workspace on the first case: 42 MiB)
+            with pytest.raises(iso.IsoError) as e:
+                iso.iso_neighbor_alltoall_noalloc(send, recv, m, comm, alg)
+            assert e.value.status == iso.ISO_ERR_SCRATCH
+            refused.add(q)
+            continue
         iso.iso_neighbor_alltoall_noalloc(send, recv, m, comm, alg)
     assert torch.cuda.memory_allocated() == before
+    assert len(refused) <= 1 and (not refused or alg == iso.ISO_ALG_COMBINED_STAGED)
     torch.cuda.synchronize()
-    for dims, offsets, m, comm, send_h, send, want, recv in prepared:
+    for q, (dims, offsets, m, comm, send_h, send, want, recv) in enumerate(prepared):
+        if q in refused:
+            assert bool((recv == 0xEE).all()), "a refused call wrote to the receive buffer"
+            continue
         assert torch.equal(recv, want), f"dims={dims} m={m} alg={alg}: differs from the persistent call"
         assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h)), f"dims={dims}: oracle"
         assert np.array_equal(send.cpu().numpy(), send_h), "send buffer was modified"
