@@ -193,8 +193,8 @@ def test_restart_and_side_stream_give_the_same_result():
                                     iso.ISO_ALG_ONEHOP: 4, iso.ISO_ALG_COMBINED_STAGED: 2}[alg]
 
 
-@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS],
-                         ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_SX_ROUNDS,
+                                 iso.ISO_ALG_COMBINED_STAGED], ids=lambda a: ALG_NAMES[a])
 def test_graph_replay_matches_eager_every_time(alg):
     """The request's graph (both forms) is replayed several times, with eager work of this
     program (fills, another eager collective) and synchronisations in between; every
