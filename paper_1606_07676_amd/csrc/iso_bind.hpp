@@ -171,6 +171,10 @@ inline void set_grid(Launch &l, uint32_t total, uint32_t k, bool eighths) {
     // (no runs: -5 % where the rank stride is a multiple of 4 KiB; runs of 512 tiles or more:
     // -8 % and worse, the last incomplete span leaves XCDs idle).
     uint32_t run_log2 = 7;
+    // (the staged schedule's kernels: a tile is 32 KiB and there are few of them; with runs of 128 a grid
+    // padded to whole spans had up to 18 % workgroups without a tile, which cost 7 % at 16-byte blocks; runs
+    // of 4 ... 32 tiles measure alike)
+    if (l.kernel == kStagedRoundKernel || l.kernel == kDeliverKernel) run_log2 = 3;
     while (run_log2 > 0 && (8u << run_log2) > n_tiles) --run_log2;
     const uint32_t span = 8u << run_log2;
     l.grid = (uint32_t)((((uint64_t)n_tiles + span - 1) / span) * span);

@@ -583,9 +583,9 @@ __global__ __launch_bounds__(kThreads) void staged_round_kernel(const StagedRoun
     typedef typename Unaligned<V>::type UV;
     typedef const UV __attribute__((address_space(1))) *src_ptr;
     typedef UV __attribute__((address_space(1))) *dst_ptr;
-    const EntryTable<true> table(a.entries, a.k, lds);
     uint32_t tile_id;
-    if (!tile_of_block(a.map, tile_id)) return;
+    if (!tile_of_block(a.map, tile_id)) return;          // (before anything is loaded: the grid is padded)
+    const EntryTable<true> table(a.entries, a.k, lds);
     const uint32_t R0 = tile_id * a.ranks;
     const uint32_t n = a.p - R0 < a.ranks ? a.p - R0 : a.ranks;
     const uint32_t plane = a.ranks * a.upb, pitch = plane + 1u;      // padded planes: the strided LDS writes spread over the banks
@@ -674,10 +674,10 @@ __global__ __launch_bounds__(kThreads) void deliver_kernel(const DeliverArgs a) 
     typedef typename Unaligned<V>::type UV;
     typedef const UV __attribute__((address_space(1))) *src_ptr;
     typedef UV __attribute__((address_space(1))) *dst_ptr;
+    uint32_t tile_id;
+    if (!tile_of_block(a.map, tile_id)) return;          // (before anything is loaded: the grid is padded)
     for (uint32_t w = threadIdx.x; w < a.s * 4u; w += kThreads) ((vec16_t *)lds)[w] = ((const vec16_t *)a.entries)[w];
     __syncthreads();
-    uint32_t tile_id;
-    if (!tile_of_block(a.map, tile_id)) return;
     const uint32_t R0 = tile_id * a.ranks;
     const uint32_t n = a.p - R0 < a.ranks ? a.p - R0 : a.ranks;
     const uint32_t plane = a.ranks * a.upb, pitch = plane + 1u;
