@@ -85,8 +85,12 @@ enum iso_algorithm {
      * receive buffer that cannot wait (its block is read again, or its source is
      * overwritten later: allgather trie nodes) goes to an extra workspace slot and is
      * copied from there by the last launch; the workspace grows by one plane of
-     * p*m bytes per such block.  Rounds left empty disappear.  Not available on a
-     * mesh (ISO_ERR_ARG). */
+     * p*m bytes per such block.  Rounds left empty disappear.  The row-writing
+     * launch takes equal blocks that are multiples of 16 bytes in dense rank-major
+     * rows with s <= 128 and s*m <= 32 KiB; any other request runs the same plan on
+     * the general kernels, the last launch as one launch per dimension (so the
+     * request's launches can exceed the plan's rounds).  Not available on a mesh
+     * (ISO_ERR_ARG). */
     ISO_ALG_COMBINED_STAGED = 5
 };
 
