@@ -61,9 +61,9 @@ int main() {
             ref(d, dims, periodic, s, rel, m, op == 1, send_h, want);
             uint8_t *send_d, *recv_d; CK(hipMalloc(&send_d, send_bytes + 16)); CK(hipMalloc(&recv_d, recv_bytes + 16));
             CK(hipMemcpy(send_d, send_h.data(), send_bytes, hipMemcpyHostToDevice));
-            for (int alg = 0; alg <= ISO_ALG_ONEHOP; ++alg) {
+            for (int alg = 0; alg <= ISO_ALG_COMBINED_STAGED; ++alg) {
                 size_t wsb = 0; int ws = iso_workspace_bytes(comm, op, alg, m, &wsb);
-                if (alg == ISO_ALG_ONEHOP && mesh && ci.d > 0) {
+                if ((alg == ISO_ALG_ONEHOP || alg == ISO_ALG_COMBINED_STAGED) && mesh && ci.d > 0) {
                     bool any_np = false; for (int j = 0; j < d; ++j) any_np |= !periodic[j];
                     if (any_np) { REQUIRE(ws == ISO_ERR_ARG); continue; }
                 }
@@ -131,7 +131,7 @@ int main() {
             }
             uint8_t *send_d, *recv_d; CK(hipMalloc(&send_d, send_h.size() + 16)); CK(hipMalloc(&recv_d, want.size() + 16));
             CK(hipMemcpy(send_d, send_h.data(), send_h.size(), hipMemcpyHostToDevice));
-            for (int alg = 0; alg <= ISO_ALG_ONEHOP; ++alg) {
+            for (int alg = 0; alg <= ISO_ALG_COMBINED_STAGED; ++alg) {
                 size_t wsb = 0; REQUIRE(iso_workspace_bytes_v(comm, 0, alg, sizes.data(), &wsb) == ISO_SUCCESS);
                 uint8_t *work_d; CK(hipMalloc(&work_d, wsb + 16)); CK(hipMemset(recv_d, 0xEE, want.size()));
                 iso_request_t rq = nullptr;
