@@ -560,7 +560,11 @@ __global__ __launch_bounds__(kThreads) void mesh_shift_round_kernel(const MeshAr
 // of one rank where the source is a rank-major buffer, rank after rank of one plane where it is a
 // slot-major one), eight independent loads per lane, parks them in LDS, and writes them in the
 // order that suits the destination.  Both sides then see runs of hundreds of bytes although the
-// blocks themselves may be 16 bytes.
+// blocks themselves may be 16 bytes.  In a round the tile's ranks are SOURCE ranks (the kernel
+// pushes: block e of rank S goes to rank S + v_e), so that all pieces of one send-buffer row, those
+// moving up and those moving down the dimension, are read by one workgroup and share their memory
+// lines; every destination block is still written exactly once.  The last launch below tiles by
+// destination rank instead, because it is the receive rows that it writes whole.
 constexpr uint32_t kTileUnits = 2048;                  // tiles of 512 to 2048 units measure alike (within 1 %)
 constexpr uint32_t kUnitsPerLane = kTileUnits / kThreads;
 
@@ -611,12 +615,7 @@ __global__ __launch_bounds__(kThreads) void staged_round_kernel(const StagedRoun
         r = has_unit ? r : 0u;
         c = has_unit ? c : 0u;
         const DevEntry en = table[e];
-        const uint32_t R = R0 + r;
-        const uint32_t qq = fast_div(R, a.d_inner);
-        const uint32_t rj = qq - fast_div(qq, a.d_pj) * a.pj;
-        uint32_t srcR = R - en.shift * a.inner;
-        srcR += rj < en.shift ? a.pj * a.inner : 0u;
-        const src_ptr sp = (src_ptr)(block_address(en.src, srcR, en.src_stride) + (uint64_t)c * sizeof(V));
+        const src_ptr sp = (src_ptr)(block_address(en.src, R0 + r, en.src_stride) + (uint64_t)c * sizeof(V));
         if constexpr (NTL && sizeof(V) == 16) regs[it] = __builtin_nontemporal_load(sp);
         else regs[it] = *sp;
         at[it] = has_unit ? e * pitch + r * a.upb + c : ~0u;
@@ -633,7 +632,13 @@ __global__ __launch_bounds__(kThreads) void staged_round_kernel(const StagedRoun
         fast_divmod(rem, a.d_upb, r, c);
         if (q < n_all && r < n) {
             const DevEntry en = table[e];
-            const dst_ptr dp = (dst_ptr)(block_address(en.dst, R0 + r, en.dst_stride) + (uint64_t)c * sizeof(V));
+            // the tile's ranks are source ranks S: the block goes to the rank `shift` steps on
+            const uint32_t S = R0 + r;
+            const uint32_t qq = fast_div(S, a.d_inner);
+            const uint32_t sj = qq - fast_div(qq, a.d_pj) * a.pj;
+            uint32_t R = S + en.shift * a.inner;
+            R -= sj + en.shift >= a.pj ? a.pj * a.inner : 0u;
+            const dst_ptr dp = (dst_ptr)(block_address(en.dst, R, en.dst_stride) + (uint64_t)c * sizeof(V));
             if constexpr (sizeof(V) == 16) __builtin_nontemporal_store(tile[e * pitch + rem], dp);
             else *dp = tile[e * pitch + rem];
         }
