@@ -50,6 +50,7 @@ struct Launch {
     MeshArgs mesh_shift;
     DeliverArgs deliver;
     StagedRoundArgs staged;
+    uint32_t tile_units;   // the staged schedule's kernels: kTileUnits or kSmallTileUnits
 };
 
 // Sizes and displacements (bytes) of the s blocks inside one rank's send and
@@ -258,12 +259,20 @@ KernelRef select_block(const Launch &l) {
 
 inline KernelRef select_kernel(int vector_bytes, const Launch &l) {
     if (l.kernel == kStagedRoundKernel) {                 // blocks of whole 16-byte units only
-        if (l.stream_loads) return {(const void *)&staged_round_kernel<vec16_t, true, kUnitsPerLane>, &l.staged};
-        return {(const void *)&staged_round_kernel<vec16_t, false, kUnitsPerLane>, &l.staged};
+        if (l.tile_units == kSmallTileUnits) {
+            if (l.stream_loads) return {(const void *)&staged_round_kernel<vec16_t, true, kSmallTileUnits / kThreads>, &l.staged};
+            return {(const void *)&staged_round_kernel<vec16_t, false, kSmallTileUnits / kThreads>, &l.staged};
+        }
+        if (l.stream_loads) return {(const void *)&staged_round_kernel<vec16_t, true, kTileUnits / kThreads>, &l.staged};
+        return {(const void *)&staged_round_kernel<vec16_t, false, kTileUnits / kThreads>, &l.staged};
     }
     if (l.kernel == kDeliverKernel) {
-        if (l.stream_loads) return {(const void *)&deliver_kernel<vec16_t, true, kUnitsPerLane>, &l.deliver};
-        return {(const void *)&deliver_kernel<vec16_t, false, kUnitsPerLane>, &l.deliver};
+        if (l.tile_units == kSmallTileUnits) {
+            if (l.stream_loads) return {(const void *)&deliver_kernel<vec16_t, true, kSmallTileUnits / kThreads>, &l.deliver};
+            return {(const void *)&deliver_kernel<vec16_t, false, kSmallTileUnits / kThreads>, &l.deliver};
+        }
+        if (l.stream_loads) return {(const void *)&deliver_kernel<vec16_t, true, kTileUnits / kThreads>, &l.deliver};
+        return {(const void *)&deliver_kernel<vec16_t, false, kTileUnits / kThreads>, &l.deliver};
     }
     if (l.kernel == kBlockKernel) {
         if (l.mesh) return l.lds_table ? select_block<true, true>(l) : select_block<false, true>(l);
@@ -518,7 +527,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 da.p = (uint32_t)p;
                 da.s = (uint32_t)s;
                 da.upb = (uint32_t)st_upb;
-                da.ranks = (uint32_t)std::min<uint64_t>(p, kTileUnits / (s * st_upb));
+                l.tile_units = s * st_upb <= kSmallTileUnits ? kSmallTileUnits : kTileUnits;
+                da.ranks = (uint32_t)std::min<uint64_t>(p, l.tile_units / (s * st_upb));
                 da.dst = (uint64_t)(uintptr_t)recvbuf;
                 while (prefixes.size() % 4) prefixes.push_back(0);            // 16-byte aligned entries
                 pd.first_prefix = prefixes.size();
@@ -563,7 +573,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 sa.p = (uint32_t)p;
                 sa.k = k;
                 sa.upb = (uint32_t)st_upb;
-                sa.ranks = (uint32_t)std::min<uint64_t>(p, kTileUnits / (k * st_upb));
+                l.tile_units = k * st_upb <= kSmallTileUnits ? kSmallTileUnits : kTileUnits;
+                sa.ranks = (uint32_t)std::min<uint64_t>(p, l.tile_units / (k * st_upb));
                 const bool shift = r.kind == ISO_ROUND_SHIFT;
                 sa.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
                 sa.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;

@@ -424,11 +424,11 @@ def test_sx_init_calls_are_the_straightforward_algorithm(mode):
 
 
 @pytest.mark.parametrize("s,m", [(128, 256), (128, 16), (127, 256), (129, 16), (26, 1264), (26, 1248), (5, 6560), (1, 32768),
-                                 (1, 32784)])
+                                 (1, 32784), (64, 256), (65, 256), (1, 16384), (1, 16400)])
 def test_staged_schedule_at_the_limits_of_its_tiles(s, m):
     """The staged schedule's own kernels take up to 128 neighbours and rows of up to 2048 units of 16 bytes
-    (one tile); one more neighbour or unit and the same plan runs on the general kernels.  Both sides of
-    both limits, on a torus whose rank count (105) is no multiple of any tile's rank count, against the
+    (one tile; rows of up to 1024 units use a smaller tile); one more neighbour or unit and the same plan
+    runs on the general kernels.  Both sides of these limits, on a torus whose rank count (105) is no multiple of any tile's rank count, against the
     oracle, every byte; and a single process."""
     for dims in ((7, 5, 3), (1, 1, 1)):
         p = int(np.prod(dims))
