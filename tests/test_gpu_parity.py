@@ -441,3 +441,39 @@ def test_staged_schedule_at_the_limits_of_its_tiles(s, m):
         one_h = gen.allgather_send(12, p, m)
         recv, info = _run(dims, offsets, iso.ISO_OP_ALLGATHER, iso.ISO_ALG_COMBINED_STAGED, m, torch.from_numpy(one_h).to(DEV))
         assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, one_h)), (dims, s, m)
+
+
+def test_requests_in_flight_together_on_several_streams():
+    """Persistent requests share nothing: eight of them (different tori, algorithms and collectives), each
+    started five times in turn on a stream of its own with no synchronisation in between, give the
+    oracle's bytes."""
+    shapes = [((8, 8), gen.moore(2, 1), 32), ((6, 5, 7), gen.moore(3, 1), 16), ((37, 11), gen.moore(2, 2), 48),
+              ((4, 4, 4, 4), gen.von_neumann(4, 1), 272)]
+    algs = [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_STAGED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_SX_FUSED]
+    live = []
+    for q, (dims, offsets, m) in enumerate(shapes):
+        p, s = int(np.prod(dims)), len(offsets)
+        comm = _comm(dims, offsets)
+        for op in (iso.ISO_OP_ALLTOALL, iso.ISO_OP_ALLGATHER):
+            alg = algs[(q + op) % len(algs)]
+            if op == iso.ISO_OP_ALLTOALL:
+                send_h = gen.alltoall_send(40 + q, p, s, m)
+                want = orc.alltoall(dims, offsets, send_h)
+                init = iso.iso_neighbor_alltoall_init
+            else:
+                send_h = gen.allgather_send(40 + q, p, m)
+                want = orc.allgather(dims, offsets, send_h)
+                init = iso.iso_neighbor_allgather_init
+            send = torch.from_numpy(send_h).to(DEV)
+            recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=DEV)
+            wsb = iso.iso_workspace_bytes(comm, op, alg, m)
+            work = torch.empty(max(wsb, 16), dtype=torch.uint8, device=DEV)
+            live.append((init(send, recv, m, work, comm, alg), torch.cuda.Stream(), send, recv, work, want, (dims, op, alg)))
+    torch.cuda.synchronize()
+    for _ in range(5):
+        for req, stream, *_ in live:
+            iso.iso_start(req, stream)
+    for req, stream, send, recv, work, want, what in live:
+        iso.iso_wait(req)
+        assert np.array_equal(recv.cpu().numpy(), want), what
+        iso.iso_request_free(req)
