@@ -231,8 +231,16 @@ KernelRef select_regular(const Launch &l) {
     }
     if constexpr (sizeof(V) == 16) {
         if (l.uniform_waves) {
+            if (l.shift.group) {
+                if (l.stream_loads) return {(const void *)&shift_round_uniform_kernel<true, true>, &l.shift};
+                return {(const void *)&shift_round_uniform_kernel<false, true>, &l.shift};
+            }
             if (l.stream_loads) return {(const void *)&shift_round_uniform_kernel<true>, &l.shift};
             return {(const void *)&shift_round_uniform_kernel<false>, &l.shift};
+        }
+        if (l.shift.group) {
+            if (l.stream_loads) return {(const void *)&shift_round_kernel<V, LDS, true, TAIL, true>, &l.shift};
+            return {(const void *)&shift_round_kernel<V, LDS, false, TAIL, true>, &l.shift};
         }
         if (l.stream_loads) return {(const void *)&shift_round_kernel<V, LDS, true, TAIL>, &l.shift};
     }
@@ -684,6 +692,16 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                     l.shift.d_k = dk;
                     l.shift.d_p = dp;
                     l.shift.entry_major = lay.slot_major || all_planes;
+                    // blocks of 2 KiB and more on rank-major buffers: groups of 64 ranks (three tori: 2 KiB -1 to
+                    // -3 % of the step, 4 KiB 0 to -3 %, 8 KiB -5 %; at 1 KiB and below between -1.5 and +1 %:
+                    // left alone.  Groups of 32 to 256 ranks measure alike, smaller ones do nothing)
+                    constexpr uint32_t kRankGroup = 64;
+                    if (!l.shift.entry_major && size0 >= 2048 && p >= kRankGroup) {
+                        l.shift.group = kRankGroup;
+                        l.shift.grouped = (uint32_t)((p / kRankGroup) * kRankGroup * k);
+                        l.shift.d_group_k = make_fastdiv(kRankGroup * k);
+                        l.shift.d_group = make_fastdiv(kRankGroup);
+                    }
                     l.shift.last_offset = size0 - width;
                     l.shift.d_inner = make_fastdiv(l.shift.inner);
                     l.shift.d_pj = make_fastdiv(l.shift.pj);

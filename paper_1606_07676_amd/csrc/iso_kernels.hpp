@@ -89,6 +89,12 @@ struct ShiftArgs {
     uint32_t entry_major;  // unit order (entry, rank, chunk) instead of (rank, entry, chunk)
     FastDiv d_chunks, d_k, d_inner, d_pj, d_p;
     uint64_t last_offset;  // block size - unit width (read by the TAIL instantiations only)
+    // Large blocks on rank-major buffers: the ranks are taken in groups of `group`, and inside a group the
+    // order is (entry, rank, chunk), so that a plane of the workspace sees `group` consecutive blocks at a
+    // time instead of one (0: no groups).  `grouped` = the blocks of all whole groups, (p / group) * group * k;
+    // the ranks after them keep the plain order.
+    uint32_t group, grouped;
+    FastDiv d_group_k, d_group;   // group * k; group
 };
 
 struct VectorArgs {
@@ -241,7 +247,7 @@ __device__ __forceinline__ void fetch_now(const ShiftArgs &a) {
     fetch_now(a.d_p);
 }
 
-template <typename V, bool LDS, bool NTL, bool TAIL>
+template <typename V, bool LDS, bool NTL, bool TAIL, bool GROUPS = false>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
@@ -251,8 +257,21 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
-    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
-    else fast_divmod(t, a.d_k, R, e);
+    if constexpr (GROUPS) {                             // an instantiation of its own: the few scalar loads and
+        if (t < a.grouped) {                            // the branch cost the plain one 2 - 3 % on small blocks
+            uint32_t g, in_group, rg;
+            fast_divmod(t, a.d_group_k, g, in_group);
+            fast_divmod(in_group, a.d_group, e, rg);
+            R = g * a.group + rg;
+        } else {
+            fast_divmod(t - a.grouped, a.d_k, R, e);
+            R += fast_div(a.grouped, a.d_k);            // the ranks of the whole groups come first
+        }
+    } else if (a.entry_major) {
+        fast_divmod(t, a.d_p, e, R);
+    } else {
+        fast_divmod(t, a.d_k, R, e);
+    }
     const uint32_t q = fast_div(R, a.d_inner);
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
     const DevEntry en = table[e];
@@ -269,7 +288,7 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
 // and are computed once, in scalar registers, the entry fetched with scalar loads.  No staging of the
 // table through LDS, no barrier, no vector-memory access in front of the one load that matters: what
 // bounds these kernels is how long a wavefront holds its slot before that load is under way.
-template <bool NTL>
+template <bool NTL, bool GROUPS = false>
 __global__ __launch_bounds__(kThreads) void shift_round_uniform_kernel(const ShiftArgs a) {
     fetch_now(a);
     uint32_t tile;
@@ -279,8 +298,21 @@ __global__ __launch_bounds__(kThreads) void shift_round_uniform_kernel(const Shi
     if (u0 >= a.total) return;                                       // total is a multiple of 64
     uint32_t t, ch0, R, e;
     fast_divmod(u0, a.d_chunks, t, ch0);
-    if (a.entry_major) fast_divmod(t, a.d_p, e, R);
-    else fast_divmod(t, a.d_k, R, e);
+    if constexpr (GROUPS) {
+        if (t < a.grouped) {
+            uint32_t g, in_group, rg;
+            fast_divmod(t, a.d_group_k, g, in_group);
+            fast_divmod(in_group, a.d_group, e, rg);
+            R = g * a.group + rg;
+        } else {
+            fast_divmod(t - a.grouped, a.d_k, R, e);
+            R += fast_div(a.grouped, a.d_k);
+        }
+    } else if (a.entry_major) {
+        fast_divmod(t, a.d_p, e, R);
+    } else {
+        fast_divmod(t, a.d_k, R, e);
+    }
     const uint32_t q = fast_div(R, a.d_inner);
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;
     // the table is never written while a collective runs: read it as constant memory, through the scalar cache

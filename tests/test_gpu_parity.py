@@ -477,3 +477,22 @@ def test_requests_in_flight_together_on_several_streams():
         iso.iso_wait(req)
         assert np.array_equal(recv.cpu().numpy(), want), what
         iso.iso_request_free(req)
+
+
+@pytest.mark.parametrize("alg", [iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_ONEHOP, iso.ISO_ALG_COMBINED_STAGED],
+                         ids=lambda a: ALG_NAMES[a])
+@pytest.mark.parametrize("dims,m", [((7, 5, 3), 4096), ((37, 11), 4100), ((64,), 8192), ((5, 13), 4097), ((3, 3, 7), 16384),
+                                    ((7, 5, 3), 2048), ((37, 11), 3072), ((13, 5), 2064)])
+def test_large_blocks_are_taken_in_groups_of_ranks(dims, m, alg):
+    """Blocks of 2 KiB and more on rank-major buffers: the round kernels (the general one, and the one
+    for blocks of whole wavefronts at 2 and 3 KiB) walk the ranks in groups of 64 (inside a group entry
+    after entry).  Rank counts that are no multiple of 64 (a last partial group),
+    exactly 64 and below 64; block sizes with and without an overlapping last unit; every byte."""
+    offsets = gen.moore(len(dims), 1) + [(0,) * len(dims)]
+    p, s = int(np.prod(dims)), len(offsets)
+    send_h = gen.alltoall_send(21, p, s, m)
+    recv, info = _run(dims, offsets, iso.ISO_OP_ALLTOALL, alg, m, torch.from_numpy(send_h).to(DEV))
+    assert np.array_equal(recv.cpu().numpy(), orc.alltoall(dims, offsets, send_h))
+    one_h = gen.allgather_send(22, p, m)
+    recv, info = _run(dims, offsets, iso.ISO_OP_ALLGATHER, alg, m, torch.from_numpy(one_h).to(DEV))
+    assert np.array_equal(recv.cpu().numpy(), orc.allgather(dims, offsets, one_h))
