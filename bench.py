@@ -12,7 +12,9 @@ Default run: the headline numbers (`value`, `roofline`, `cpu_baseline`) are take
 the largest workload, config 5 (8^5 torus, 40 neighbours, 4 KiB blocks, 5.4 GB per
 buffer); the other workloads whose blocks are at least 128 bytes (configs 2, 3 and
 4) are timed the same way in the same run and reported under `workloads`, each with
-its own roofline and CPU baseline.  `--config N` times one workload only.
+its own roofline and CPU baseline; `small_blocks` lists config 4's torus at 16, 32
+and 64 bytes with the plain and the staged schedule, and `comparison` (on config 2)
+the other algorithms, layouts and interfaces.  `--config N` times one workload only.
 """
 import argparse
 import glob
