@@ -569,3 +569,21 @@ def test_sizes_that_would_overflow_are_refused():
         iso.iso_plan_create(far, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_ONEHOP)
     assert e.value.status == iso.ISO_ERR_TOO_LARGE
     assert iso.iso_plan_info(iso.iso_plan_create(far, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED))["launches"] == 2   # a same-rank copy (70000 = 0 mod 5) and one shift
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/iso.h is the boundary of a C ABI: a C99 compiler must take it as it is, pedantically."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if not gcc:
+        pytest.skip("no gcc")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_iso_h.c"
+    src.write_text('#include "iso.h"\n'
+                   "int main(void) { iso_plan_entry_t e; iso_comm_info_t c; e.dim = ISO_ROUND_DELIVER; c.d = e.dim;\n"
+                   "  return c.d == ISO_ALG_COMBINED_STAGED ? 1 : 0; }\n")
+    out = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                          "-c", str(src), "-o", str(tmp_path / "use_iso_h.o")],
+                         stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert out.returncode == 0, out.stdout
