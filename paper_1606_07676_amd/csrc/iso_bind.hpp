@@ -337,6 +337,79 @@ inline int store_table(const StaticArena &arena, size_t at, const void *host, si
     return ISO_SUCCESS;
 }
 
+// One entry of a launch on the host: the device entry, the block's size, and for the staged schedule's last
+// launch the dimension the entry moves along and the receive block it writes.
+struct HostEntry {
+    DevEntry de;
+    uint64_t size;
+    int dim, dst_slot;
+};
+
+// Mesh shift launches of equal blocks: one bit per tile of kThreads units, set where every rank of the tile has
+// a source for every entry of the launch.  Coordinates at which every entry finds its source: r_l - c_l in
+// [0, p_l) for all masked dimensions l of all entries.  A tile is interior if its ranks share all coordinates
+// but the last and lie inside these bounds (conservative: a tile that crosses into the next row of the last
+// dimension counts as not interior).
+inline std::vector<uint32_t> mesh_interior_tiles(const Comm &c, bool slot_major, const HostEntry *ents, uint32_t k,
+                                                 uint64_t total, uint64_t chunks, uint64_t p) {
+    std::vector<int64_t> in_lo((size_t)c.d, 0), in_hi((size_t)c.d, 0);
+    bool has_interior = true;
+    for (int j = 0; j < c.d; ++j) {
+        int64_t lo = 0, hi = c.dims[j];
+        for (uint32_t q = 0; q < k; ++q) {
+            const DevEntry &de = ents[q].de;
+            if (!(((de.meta >> 8) >> j) & 1u)) continue;
+            const int64_t cl = c.c((int)de.ref, j);
+            lo = std::max<int64_t>(lo, cl);
+            hi = std::min<int64_t>(hi, (int64_t)c.dims[j] + cl);
+        }
+        if (lo >= hi) has_interior = false;
+        in_lo[(size_t)j] = lo;
+        in_hi[(size_t)j] = hi;
+    }
+    const uint64_t n_tiles = (total + kThreads - 1) / kThreads;
+    std::vector<uint32_t> bits((size_t)((n_tiles + 31) / 32), 0u);
+    for (uint64_t tl = 0; has_interior && tl < n_tiles; ++tl) {
+        const uint64_t u0 = tl * kThreads, u1 = std::min<uint64_t>(u0 + kThreads, total) - 1;
+        const uint64_t t0 = u0 / chunks, t1 = u1 / chunks;
+        uint64_t R0, R1;
+        if (slot_major) {                      // (entry, rank, chunk): one entry per interior tile
+            if (t0 / p != t1 / p) continue;
+            R0 = t0 % p;
+            R1 = t1 % p;
+        } else {                               // (rank, entry, chunk)
+            R0 = t0 / k;
+            R1 = t1 / k;
+        }
+        uint64_t rem = R0;
+        bool inside = true;
+        for (int j = c.d - 1; j >= 0 && inside; --j) {
+            const int64_t r = (int64_t)(rem % (uint64_t)c.dims[j]);
+            rem /= (uint64_t)c.dims[j];
+            const int64_t last = j == c.d - 1 ? r + (int64_t)(R1 - R0) : r;
+            inside = r >= in_lo[(size_t)j] && last < in_hi[(size_t)j];
+        }
+        if (inside) bits[(size_t)(tl >> 5)] |= 1u << (tl & 31);
+    }
+    return bits;
+}
+
+// The record of one entry of the staged schedule's last launch.
+inline DeliverEntry make_deliver_entry(const Comm &c, const HostEntry &he) {
+    DeliverEntry x{};
+    x.src = he.de.src;
+    x.src_stride = he.de.src_stride;
+    x.slot = (uint32_t)he.dst_slot;
+    const uint32_t inner = he.dim < 0 ? 1u : (uint32_t)c.inner[(size_t)he.dim];
+    x.pj = he.dim < 0 ? 1u : (uint32_t)c.dims[(size_t)he.dim];
+    x.shift = he.dim < 0 ? 0u : he.de.shift;
+    x.back = x.shift * inner;
+    x.wrap = x.pj * inner;
+    x.d_inner = make_fastdiv(inner);
+    x.d_pj = make_fastdiv(x.pj);
+    return x;
+}
+
 // Checks the buffers, builds the device table and the launch list.  `rq.plan`
 // must already hold the schedule.
 // With `arena` the table is placed there instead of in an allocation of its own, and the workspace is
@@ -450,7 +523,6 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
     }
 
     // all entries, with their own unit width
-    struct HostEntry { DevEntry de; uint64_t size; int dim, dst_slot; };
     std::vector<std::vector<HostEntry>> rounds(bound_rounds.size());
     bool uniform = true;
     uint64_t size0 = 0;
@@ -543,17 +615,7 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 for (int rows = 1; rows >= 0; --rows)                          // rank-major sources first
                     for (const HostEntry &he : ents) {
                         if ((he.de.src_stride > size0) != (rows == 1)) continue;
-                        DeliverEntry x{};
-                        x.src = he.de.src;
-                        x.src_stride = he.de.src_stride;
-                        x.slot = (uint32_t)he.dst_slot;
-                        const uint32_t inner = he.dim < 0 ? 1u : (uint32_t)c.inner[(size_t)he.dim];
-                        x.pj = he.dim < 0 ? 1u : (uint32_t)c.dims[(size_t)he.dim];
-                        x.shift = he.dim < 0 ? 0u : he.de.shift;
-                        x.back = x.shift * inner;
-                        x.wrap = x.pj * inner;
-                        x.d_inner = make_fastdiv(inner);
-                        x.d_pj = make_fastdiv(x.pj);
+                        const DeliverEntry x = make_deliver_entry(c, he);
                         da.k_rows += rows == 1;
                         const uint32_t *words = (const uint32_t *)&x;
                         prefixes.insert(prefixes.end(), words, words + sizeof(x) / 4);
@@ -640,49 +702,8 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                         ma.d_dims[j] = make_fastdiv((uint32_t)c.dims[j]);
                         ma.inner_of[j] = (uint32_t)c.inner[j];
                     }
-                    // Coordinates at which every entry of the launch finds its source: r_l - c_l in [0, p_l)
-                    // for all masked dimensions l of all entries.  A tile is interior if its ranks share
-                    // all coordinates but the last and lie inside these bounds (conservative: a tile that
-                    // crosses into the next row of the last dimension counts as not interior).
-                    std::vector<int64_t> in_lo((size_t)c.d, 0), in_hi((size_t)c.d, 0);
-                    bool has_interior = true;
-                    for (int j = 0; j < c.d; ++j) {
-                        int64_t lo = 0, hi = c.dims[j];
-                        for (uint32_t q = 0; q < k; ++q) {
-                            const DevEntry &de = ents[done + q].de;
-                            if (!(((de.meta >> 8) >> j) & 1u)) continue;
-                            const int64_t cl = c.c((int)de.ref, j);
-                            lo = std::max<int64_t>(lo, cl);
-                            hi = std::min<int64_t>(hi, (int64_t)c.dims[j] + cl);
-                        }
-                        if (lo >= hi) has_interior = false;
-                        in_lo[(size_t)j] = lo;
-                        in_hi[(size_t)j] = hi;
-                    }
-                    const uint64_t n_tiles = (total + kThreads - 1) / kThreads;
-                    std::vector<uint32_t> bits((size_t)((n_tiles + 31) / 32), 0u);
-                    for (uint64_t tl = 0; has_interior && tl < n_tiles; ++tl) {
-                        const uint64_t u0 = tl * kThreads, u1 = std::min<uint64_t>(u0 + kThreads, total) - 1;
-                        const uint64_t t0 = u0 / chunks, t1 = u1 / chunks;
-                        uint64_t R0, R1;
-                        if (lay.slot_major) {              // (entry, rank, chunk): one entry per interior tile
-                            if (t0 / p != t1 / p) continue;
-                            R0 = t0 % p;
-                            R1 = t1 % p;
-                        } else {                           // (rank, entry, chunk)
-                            R0 = t0 / k;
-                            R1 = t1 / k;
-                        }
-                        uint64_t rem = R0;
-                        bool inside = true;
-                        for (int j = c.d - 1; j >= 0 && inside; --j) {
-                            const int64_t r = (int64_t)(rem % (uint64_t)c.dims[j]);
-                            rem /= (uint64_t)c.dims[j];
-                            const int64_t last = j == c.d - 1 ? r + (int64_t)(R1 - R0) : r;
-                            inside = r >= in_lo[(size_t)j] && last < in_hi[(size_t)j];
-                        }
-                        if (inside) bits[(size_t)(tl >> 5)] |= 1u << (tl & 31);
-                    }
+                    const std::vector<uint32_t> bits =
+                        mesh_interior_tiles(c, lay.slot_major, ents.data() + done, k, total, chunks, p);
                     prefixes.insert(prefixes.end(), bits.begin(), bits.end());
                 } else {
                     const bool shift = r.kind == ISO_ROUND_SHIFT;
