@@ -41,6 +41,7 @@ struct Launch {
     bool stream_loads;     // every source block is read exactly once in this launch: non-temporal loads
     bool tail;             // regular kernels: the last unit of a block overlaps the one before it
     bool uniform_waves;    // shift kernel, 16-byte units, blocks a multiple of 64 units: one block per wavefront
+    bool block_groups;     // block kernel: ranks taken in groups of kBlockGroup
     int round;             // the plan's round this launch belongs to (a large round is split over several launches)
     uint32_t dyn_lds;      // bytes of dynamic LDS (the kernels of the staged schedule: their tile)
 
@@ -261,6 +262,10 @@ KernelRef select_width(const Launch &l) {
 
 template <bool LDS, bool MESH>
 KernelRef select_block(const Launch &l) {
+    if (l.block_groups) {
+        if (l.stream_loads) return {(const void *)&block_round_kernel<LDS, MESH, true, true>, &l.block};
+        return {(const void *)&block_round_kernel<LDS, MESH, false, true>, &l.block};
+    }
     if (l.stream_loads) return {(const void *)&block_round_kernel<LDS, MESH, true>, &l.block};
     return {(const void *)&block_round_kernel<LDS, MESH, false>, &l.block};
 }
@@ -764,6 +769,15 @@ inline int bind_request(BoundRequest &rq, const Comm &c, const Layout &lay, cons
                 b.d_plane = make_fastdiv(b.equal_units ? (uint32_t)(p * b.equal_units) : 1u);
                 b.vector_round = r.kind == ISO_ROUND_VECTOR;
                 b.d_row = make_fastdiv((uint32_t)row_units);
+                // shift rounds on rank-major buffers: ranks in groups (not the staged schedule, whose tiny
+                // blocks travel through dense planes: +1 % there; not the s-exchange: +1 to +3 %)
+                if (!entry_major && r.kind != ISO_ROUND_VECTOR && pl.algorithm != ISO_ALG_COMBINED_STAGED &&
+                    p >= kBlockGroup) {
+                    l.block_groups = true;
+                    b.grouped = (uint32_t)((p / kBlockGroup) * kBlockGroup * row_units);
+                    b.d_group_row = make_fastdiv((uint32_t)(row_units * kBlockGroup));
+                    b.d_plane = make_fastdiv(b.equal_units ? kBlockGroup * b.equal_units : 1u);
+                }
                 const bool shift = r.kind == ISO_ROUND_SHIFT;
                 b.inner = shift ? (uint32_t)c.inner[r.dim] : 1u;
                 b.pj = shift ? (uint32_t)c.dims[r.dim] : 1u;

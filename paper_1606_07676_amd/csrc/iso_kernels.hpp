@@ -382,7 +382,9 @@ struct BlockArgs {
     uint32_t equal_units;      // != 0: every entry of the launch has this many units (no search)
     uint32_t entry_major;      // slot-major buffers: units ordered (entry, rank, unit) and prefix[e] counts
                                // the units of all ranks before entry e; else (rank, entry, unit)
-    FastDiv d_row, d_inner, d_pj, d_units, d_plane;   // d_plane: p * equal_units
+    uint32_t grouped;          // GROUPS: units of the ranks that form whole groups (the first ones)
+    FastDiv d_row, d_inner, d_pj, d_units, d_plane;   // d_plane: p * equal_units (GROUPS: group * equal_units)
+    FastDiv d_group_row;       // GROUPS: units of a group's rows
     FastDiv d_dims[ISO_MAX_DIMS];
     uint32_t inner_of[ISO_MAX_DIMS];
 };
@@ -467,7 +469,15 @@ __device__ __forceinline__ bool mesh_source_rank(const Args &a, const DevEntry &
     return has_source;
 }
 
-template <bool LDS, bool MESH, bool NTL>
+// GROUPS (rank-major buffers, shift rounds): the ranks are taken in groups of kBlockGroup, and inside
+// a group the units are ordered (entry, rank, unit) as on slot-major buffers, so that large and tiny
+// blocks fall into different workgroups and a workgroup's wide units are not held up by a second
+// pass for narrow ones; prefix[] still counts one row's units.  Ranks beyond the last whole group
+// are taken one by one.  (Stencil-shaped all-to-all on 32 x 32 x 32, blocks of 4096 / 64 / 1 bytes:
+// groups of 8 ranks -4 % of the step, 32 -5 %, 64 -6.5 %, 128 and 256 -7.5 %, 1024 -7 %.)
+constexpr uint32_t kBlockGroupLog2 = 7, kBlockGroup = 1u << kBlockGroupLog2;
+
+template <bool LDS, bool MESH, bool NTL, bool GROUPS = false>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
@@ -483,28 +493,45 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     if (u >= a.total) return;
     // flat index -> rank R, entry lo, unit ch of that entry's block
     uint32_t R = 0, lo = 0, ch = 0, w = u;
-    if (!a.entry_major) fast_divmod(u, a.d_row, R, w);    // w: unit inside the rank's row
+    uint32_t span_log2 = 0;                                // GROUPS: w counts through 2^span_log2 rows, entry by entry
+    bool planes = a.entry_major;                           // w (then ch) counts through several ranks' blocks
+    if constexpr (GROUPS) {
+        planes = u < a.grouped;
+        if (planes) {
+            fast_divmod(u, a.d_group_row, R, w);          // R: the group, below its first rank
+            R <<= kBlockGroupLog2;
+            span_log2 = kBlockGroupLog2;
+        } else {
+            fast_divmod(u - a.grouped, a.d_row, R, w);
+            R += fast_div(a.grouped, a.d_row);
+        }
+    } else if (!a.entry_major) {
+        fast_divmod(u, a.d_row, R, w);                     // w: unit inside the rank's row
+    }
     // entry-major: w counts through the entries one after another, each with the units of all p ranks
     if (a.k == 1) {
         ch = w;
     } else if (a.equal_units) {                            // equal blocks: plain division, no search
-        fast_divmod(w, a.entry_major ? a.d_plane : a.d_units, lo, ch);
+        fast_divmod(w, planes ? a.d_plane : a.d_units, lo, ch);
     } else {
-        uint32_t hi = a.k;                                 // largest e with prefix[e] <= w
+        const uint32_t key = w >> span_log2;               // prefix[e] * 2^n <= w  <=>  prefix[e] <= w >> n
+        uint32_t hi = a.k;                                 // largest e with prefix[e] <= key
         while (hi - lo > 1) {
             const uint32_t mid = (lo + hi) >> 1;
-            if (prefix[mid] <= w) lo = mid;
+            if (prefix[mid] <= key) lo = mid;
             else hi = mid;
         }
-        ch = w - prefix[lo];
+        ch = w - (prefix[lo] << span_log2);
     }
     const DevEntry en = table[lo];
-    if (a.entry_major) {                                   // ch still counts (rank, unit) inside the plane
+    if (planes) {                                          // ch still counts (rank, unit) inside the plane
         const FastDiv by_units = a.equal_units
                                      ? a.d_units
                                      : FastDiv{prefix[a.k + 1 + lo], (en.meta >> 24) & 1u, (en.meta >> 25) & 31u, en.units};
         const uint32_t in_plane = ch;
-        fast_divmod(in_plane, by_units, R, ch);
+        uint32_t rank_in_span;
+        fast_divmod(in_plane, by_units, rank_in_span, ch);
+        R += rank_in_span;
     }
     uint32_t srcR = R;                                    // modulo 2^32, see vector_source_rank
     if constexpr (MESH) {

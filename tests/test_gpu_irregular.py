@@ -24,6 +24,8 @@ CASES = [
                  (4, 0, 1), (4, 0, 2), (4, 1, 1)]),
     ((5, 4), [(1, 1), (1, 1), (1, 1), (0, 0), (0, 0), (2, 0), (2, 0)]),
     ((37, 11), gen.moore(2, 2)),
+    ((8, 4, 4), gen.moore(3, 1)),           # shift rounds take the ranks in groups of 128
+    ((128, 3), gen.moore(2, 1)),
 ]
 
 

@@ -60,9 +60,10 @@ def test_mesh_alltoall_and_allgather_every_byte(case, alg):
         assert np.array_equal(got.cpu().numpy(), wantg), f"ag dims={dims} periodic={periodic} m={m}"
 
 
-def test_mesh_irregular_blocks_and_refused_onehop():
-    dims, periodic, offsets = (9, 7, 5), (0, 0, 1), gen.moore(3, 1)
-    p, s = 315, 26
+@pytest.mark.parametrize("dims", [(9, 7, 5), (8, 4, 4)])
+def test_mesh_irregular_blocks_and_refused_onehop(dims):
+    periodic, offsets = (0, 0, 1), gen.moore(3, 1)
+    p, s = int(np.prod(dims)), 26
     sizes = gen.stencil_block_sizes(offsets, 16)
     sd, ext = gen.packed_displacements(sizes, 16)
     rng = np.random.default_rng(3)
