@@ -15,12 +15,20 @@ buffer); the other workloads whose blocks are at least 128 bytes (configs 2, 3 a
 its own roofline and CPU baseline; `small_blocks` lists config 4's torus at 16, 32
 and 64 bytes with the plain and the staged schedule, and `comparison` (on config 2)
 the other algorithms, layouts and interfaces.  `--config N` times one workload only.
+`roofline.traffic` is counted by the run itself: after a workload is timed, two child
+runs of this program on that workload under `rocprofv3 --pmc` (FETCH_SIZE, then
+WRITE_SIZE); `--no-live-traffic` reports the recorded summary under profiles/ instead.
 """
 import argparse
+import csv
 import glob
 import json
 import os
+import shutil
+import signal
+import subprocess
 import sys
+import tempfile
 import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
@@ -64,6 +72,9 @@ def parse():
     ap.add_argument("--copy-reference", action="store_true",
                     help="with --no-extras: still run the 1 GiB plain copy (calibration of the traffic counters)")
     ap.add_argument("--cpu-seconds", type=float, default=6.0, help="CPU-oracle timing budget per workload")
+    ap.add_argument("--no-live-traffic", action="store_true",
+                    help="do not count HBM traffic in child runs under rocprofv3; `roofline.traffic` then comes "
+                         "from the recorded summary under profiles/ (implied by --timed-only)")
     ap.add_argument("--small-sweep", action="store_true",
                     help="instead of the benchmark: all-to-all on tori of about 500 processes (the paper's own "
                          "regime, Section 4), every algorithm, three block sizes; prints one JSON line")
@@ -71,14 +82,80 @@ def parse():
 
 
 def recorded_traffic(tag):
-    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summaries of
-    this same command (counters cannot be read from inside the process): the value of the
-    summary whose name carries `tag`, else None."""
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of
+    this same command (the summary whose name carries `tag`) and that file's name, else
+    (None, None).  Stands in where the traffic is not counted by the run itself."""
     for path in sorted(glob.glob(os.path.join(ROOT, "profiles", f"*{tag}_hbm_traffic.txt"))):
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return int(line.split("=")[1])
-    return None
+                return int(line.split("=")[1]), "recorded: profiles/" + os.path.basename(path)
+    return None, None
+
+
+def scaled_counter_average(csv_path, counter):
+    """From rocprofv3's counter_collection.csv: the average of `counter` (KiB per dispatch) over the
+    library's kernels other than the plain copy, scaled so that the plain copy's own average
+    reads 1 GiB = 2^20 KiB (what it moves each way), and that scale; None if either kind of
+    dispatch is missing."""
+    copy, rounds = [], []
+    for row in csv.DictReader(open(csv_path)):
+        if row["Counter_Name"] != counter or "iso::" not in row["Kernel_Name"]:
+            continue
+        (copy if "copy_kernel" in row["Kernel_Name"] else rounds).append(float(row["Counter_Value"]))
+    if not copy or not rounds:
+        return None
+    scale = (1 << 20) / (sum(copy) / len(copy))
+    return sum(rounds) / len(rounds) * scale, scale
+
+
+def counted_kib(command, counter):
+    """Runs `command` (this program with --timed-only --copy-reference) under
+    `rocprofv3 --pmc <counter>` and returns the counter's average per dispatch of the
+    library's kernels of the step, scaled by what it reads for the plain copy of 1 GiB
+    in the same run, as (KiB per launch, scale); None if the run fails."""
+    out_dir = tempfile.mkdtemp(prefix="iso_pmc_", dir="/tmp")
+    env = dict(os.environ, TMPDIR="/tmp")
+    full = ["timeout", "-s", "KILL", "150", "rocprofv3", "--pmc", counter, "--output-format", "csv",
+            "-d", out_dir, "-o", "x", "--"] + command
+    try:
+        child = subprocess.Popen(full, cwd="/tmp", env=env, stdout=subprocess.DEVNULL, stderr=subprocess.PIPE,
+                                 start_new_session=True)
+        try:
+            _, err = child.communicate(timeout=170)
+        except subprocess.TimeoutExpired:
+            os.killpg(child.pid, signal.SIGKILL)         # the group this call started, nothing else
+            child.communicate()
+            log(f"  live traffic: {counter} run exceeded its time limit")
+            return None
+        if child.returncode != 0:
+            log(f"  live traffic: {counter} run ended with status {child.returncode}: "
+                f"{err.decode(errors='replace')[-300:]}")
+            return None
+        files = glob.glob(os.path.join(out_dir, "**", "*counter_collection.csv"), recursive=True)
+        if not files:
+            return None
+        return scaled_counter_average(files[0], counter)
+    except OSError as e:                                 # no profiler on this machine
+        log(f"  live traffic: {e}")
+        return None
+    finally:
+        shutil.rmtree(out_dir, ignore_errors=True)
+
+
+def live_traffic(flags):
+    """HBM bytes per launch of the step's kernels, counted now: two child runs of this program
+    with `flags` under rocprofv3, FETCH_SIZE then WRITE_SIZE (KiB per dispatch, one counter per
+    run), each scaled by the same counter's reading for the plain 1 GiB copy.  None if either
+    run fails."""
+    command = ["python3", os.path.join(ROOT, "bench.py")] + flags + [
+        "--steps", "3", "--warmup", "1", "--timed-only", "--no-cpu-baseline", "--no-extras", "--copy-reference"]
+    fetch = counted_kib(command, "FETCH_SIZE")
+    write = counted_kib(command, "WRITE_SIZE") if fetch else None
+    if not fetch or not write:
+        return None
+    return {"bytes_per_launch": int((fetch[0] + write[0]) * 1024),
+            "fetched": int(fetch[0] * 1024), "written": int(write[0] * 1024),
+            "copy_scale": [round(fetch[1], 4), round(write[1], 4)]}
 
 
 def median(xs):
@@ -389,7 +466,7 @@ class Bench:
         roofline = {
             "kernel": kernel, "bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": recorded_traffic(tag),
+            "traffic": recorded_traffic(tag)[0], "traffic_source": recorded_traffic(tag)[1],
             "algorithmic_bytes_per_launch": int(alg_bytes_per_launch),
             "avg_launch_us": round(avg_launch_ms * 1e3, 2), "launches_per_step": self.launches,
         }
@@ -421,6 +498,18 @@ class Bench:
             if flag:
                 out["config"][key] = flag
         return out
+
+    def flags(self):
+        """The command-line flags that time this workload and variant alone."""
+        a = self.args
+        f = ["--config", str(self.gen.CONFIGS.index(self.cfg) + 1), "--m", str(self.m), "--algorithm", a.algorithm,
+             "--layout", a.layout, "--seed", str(a.seed)]
+        if a.mesh:
+            f.append("--mesh")
+        for name, value in (("--irregular", a.irregular), ("--pad", a.pad), ("--graph", a.graph)):
+            if value:
+                f += [name, str(value)]
+        return f
 
     def tag(self):
         """Names the (workload, variant) in the file names under profiles/."""
@@ -763,6 +852,20 @@ def main():
         if not args.no_cpu_baseline and b.plain:
             b.cpu_leg(res, max(args.cpu_seconds, 10.0) if idx == head_idx else args.cpu_seconds)
         b.close()
+        if not (args.timed_only or args.no_live_traffic):
+            # HBM traffic of this workload's launches, counted in child runs of this program
+            counted = live_traffic(b.flags())
+            if counted:
+                roof = res["roofline"]
+                roof["traffic"] = counted["bytes_per_launch"]
+                roof["traffic_source"] = ("counted in this run: rocprofv3 --pmc FETCH_SIZE, then WRITE_SIZE, around "
+                                          "`bench.py " + " ".join(b.flags()) + " --steps 3 --warmup 1 --timed-only "
+                                          "--no-cpu-baseline --no-extras --copy-reference`, scaled by the plain "
+                                          "1 GiB copy of the same run")
+                roof["traffic_fetched_written"] = [counted["fetched"], counted["written"]]
+                roof["traffic_copy_scale"] = counted["copy_scale"]
+                log(f"  HBM traffic per launch, counted: {counted['bytes_per_launch']} B "
+                    f"({counted['bytes_per_launch'] / roof['algorithmic_bytes_per_launch']:.4f} x algorithmic)")
         results.append(res)
         log(f"  [{time.perf_counter() - t_start:.1f} s since start]")
 

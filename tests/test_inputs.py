@@ -84,9 +84,10 @@ def test_u8_blocks_are_one_draw_per_byte():
 
 
 def test_recorded_traffic_summaries_cover_the_benchmark_workloads():
-    """bench.py cannot read hardware counters from inside the process: roofline.traffic is the value
-    of the committed rocprofv3 summary of the same workload.  Every workload of the default run has
-    one, its figures are consistent, and every summary states the command that made it."""
+    """bench.py counts roofline.traffic in child runs under rocprofv3 and, where that is switched off
+    or fails, reports the value of the committed rocprofv3 summary of the same workload.  Every
+    workload of the default run has one, its figures are consistent, and every summary states the
+    command that made it."""
     import glob
     import os
     import re
@@ -95,8 +96,8 @@ def test_recorded_traffic_summaries_cover_the_benchmark_workloads():
     sys.path.insert(0, root)
     import bench
     for tag in ("c5_m4096", "c2_m256", "c3_m1024", "c4_m128"):
-        t = bench.recorded_traffic(tag)
-        assert isinstance(t, int) and t > 0, tag
+        t, source = bench.recorded_traffic(tag)
+        assert isinstance(t, int) and t > 0 and source.startswith("recorded: profiles/"), tag
     files = sorted(glob.glob(os.path.join(root, "profiles", "*.txt")))
     assert len(files) >= 20
     for path in files:
@@ -112,4 +113,25 @@ def test_recorded_traffic_summaries_cover_the_benchmark_workloads():
         (path,) = glob.glob(os.path.join(root, "profiles", f"*{tag}_hbm_traffic.txt"))
         text = open(path).read()
         a = int(re.search(r"^algorithmic_bytes_per_launch = (\d+)", text, re.M).group(1))
-        assert abs(bench.recorded_traffic(tag) / a - 1.0) < 0.01, tag
+        assert abs(bench.recorded_traffic(tag)[0] / a - 1.0) < 0.01, tag
+
+
+def test_counter_summary_scales_by_the_plain_copy(tmp_path):
+    """The per-launch traffic that bench.py derives from a rocprofv3 counter file: kernels of the
+    step averaged, the plain copy's reading taken as 1 GiB, other counters and kernels ignored."""
+    import os
+    import sys
+    sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    import bench
+    rows = ["Kernel_Name,Counter_Name,Counter_Value",
+            '"void iso::copy_kernel(uint4*)",FETCH_SIZE,524288.0',           # reads 2 x what it counts
+            '"void iso::copy_kernel(uint4*)",FETCH_SIZE,524288.0',
+            '"void iso::shift_round_kernel<a, b>(iso::ShiftArgs)",FETCH_SIZE,1000.0',
+            '"void iso::shift_round_kernel<a, b>(iso::ShiftArgs)",FETCH_SIZE,3000.0',
+            '"void iso::shift_round_kernel<a, b>(iso::ShiftArgs)",WRITE_SIZE,77.0',
+            '"void at::native::fill_kernel()",FETCH_SIZE,999999.0']
+    path = tmp_path / "x_counter_collection.csv"
+    path.write_text("\n".join(rows) + "\n")
+    kib, scale = bench.scaled_counter_average(str(path), "FETCH_SIZE")
+    assert scale == 2.0 and kib == 4000.0
+    assert bench.scaled_counter_average(str(path), "WRITE_SIZE") is None          # no copy to scale by
