@@ -78,6 +78,9 @@ def parse():
     ap.add_argument("--small-sweep", action="store_true",
                     help="instead of the benchmark: all-to-all on tori of about 500 processes (the paper's own "
                          "regime, Section 4), every algorithm, three block sizes; prints one JSON line")
+    ap.add_argument("--setup-times", action="store_true",
+                    help="instead of the benchmark: times of the host steps (neighbourhood, schedule, init) for the "
+                         "Moore neighbourhoods of the paper's set-up table (Section 4); prints one JSON line")
     return ap.parse_args()
 
 
@@ -213,6 +216,58 @@ def small_sweep():
             log(row)
             rows.append(row)
     print(json.dumps({"small_sweep": rows}), flush=True)
+
+
+def setup_times():
+    """Section 4's set-up table carried over: full Moore neighbourhoods of radius 1 to 3 in 2 to 5
+    dimensions on a torus of 480 processes (30 x 16 there; factored evenly per dimension here).
+    Times of the host steps, median of 25 calls each, ms: iso_neighborhood_create (validation,
+    residues, round lists), the schedule computation alone (iso_plan_create, all-to-all and
+    allgather), and iso_neighbor_alltoall_init on device buffers (schedule, checks of the buffers,
+    table built and copied to the device)."""
+    import numpy as np
+    import torch
+    import iso_inputs as gen
+    import paper_1606_07676_amd as iso
+    iso.load_library()
+    dev = "cuda:0"
+    torus = {2: (24, 20), 3: (10, 8, 6), 4: (6, 5, 4, 4), 5: (5, 4, 4, 3, 2)}
+    m, reps = 8, 25
+
+    def timed(fn, free=None):
+        ts = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            obj = fn()
+            ts.append((time.perf_counter() - t0) * 1e3)
+            if free:
+                free(obj)
+        return round(median(ts), 4)
+
+    rows = []
+    for d in (2, 3, 4, 5):
+        for r in (1, 2, 3):
+            dims, offs = torus[d], np.asarray(gen.moore(d, r), np.int32)
+            p, s_n = int(np.prod(dims)), len(offs)
+            comm = iso.iso_neighborhood_create(dims, offs)
+            send = torch.zeros((p, s_n, m), dtype=torch.uint8, device=dev)
+            recv = torch.empty_like(send)
+            work = torch.empty(max(iso.iso_workspace_bytes(comm, iso.ISO_OP_ALLTOALL, iso.ISO_ALG_COMBINED, m), 16),
+                               dtype=torch.uint8, device=dev)
+            row = {"d": d, "radius": r, "dims": list(dims), "s": s_n,
+                   "iso_neighborhood_create_ms": timed(lambda: iso.iso_neighborhood_create(dims, offs)),
+                   "schedule_alltoall_ms": timed(lambda: iso.iso_plan_create(comm, iso.ISO_OP_ALLTOALL,
+                                                                            iso.ISO_ALG_COMBINED), iso.iso_plan_free),
+                   "schedule_allgather_ms": timed(lambda: iso.iso_plan_create(comm, iso.ISO_OP_ALLGATHER,
+                                                                             iso.ISO_ALG_COMBINED), iso.iso_plan_free),
+                   "iso_neighbor_alltoall_init_ms": timed(lambda: iso.iso_neighbor_alltoall_init(send, recv, m, work, comm),
+                                                          iso.iso_request_free)}
+            req = iso.iso_neighbor_alltoall_init(send, recv, m, work, comm)
+            row["rounds"] = iso.iso_request_info(req)["launches"]
+            iso.iso_request_free(req)
+            log(row)
+            rows.append(row)
+    print(json.dumps({"setup_times": rows}), flush=True)
 
 
 class Bench:
@@ -810,6 +865,9 @@ def main():
         sys.exit(1)
     if args.small_sweep:
         small_sweep()
+        return
+    if args.setup_times:
+        setup_times()
         return
     iso.load_library()
     torch.cuda.set_device(0)
