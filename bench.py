@@ -910,7 +910,9 @@ def main():
         if not args.no_cpu_baseline and b.plain:
             b.cpu_leg(res, max(args.cpu_seconds, 10.0) if idx == head_idx else args.cpu_seconds)
         b.close()
-        if not (args.timed_only or args.no_live_traffic):
+        # (not when this process itself runs under the profiler, whose settings a child would inherit)
+        profiled = any(k.startswith(("ROCPROF", "ROCP_")) for k in os.environ)
+        if not (args.timed_only or args.no_live_traffic or profiled):
             # HBM traffic of this workload's launches, counted in child runs of this program
             counted = live_traffic(b.flags())
             if counted:
