@@ -924,6 +924,10 @@ def main():
                                           "1 GiB copy of the same run")
                 roof["traffic_fetched_written"] = [counted["fetched"], counted["written"]]
                 roof["traffic_copy_scale"] = counted["copy_scale"]
+                # the same fraction on the counted bytes (the s-exchange's allgather re-reads its send blocks
+                # from the caches: there `frac`, on the requested bytes, is no HBM figure and this one is)
+                roof["frac_on_counted_traffic"] = round(
+                    counted["bytes_per_launch"] / (roof["avg_launch_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
                 log(f"  HBM traffic per launch, counted: {counted['bytes_per_launch']} B "
                     f"({counted['bytes_per_launch'] / roof['algorithmic_bytes_per_launch']:.4f} x algorithmic)")
         results.append(res)
