@@ -649,9 +649,16 @@ class Bench:
             offs = gen.moore(3, 1)
             sizes = gen.stencil_block_sizes(offs, 64)
             icomm = iso.iso_neighborhood_create(cfg.dims, offs)
-            # blocks at 16-byte aligned displacements, and packed back to back (rows of 25352 bytes)
-            for tag, align in (("", 16), ("packed_", 1)):
+            # blocks in neighbour order at 16-byte aligned displacements; packed back to back (rows of
+            # 25352 bytes); and, same row length as the first, the large blocks side by side at the start of
+            # the row with the tiny ones packed behind them (a choice of the caller's displacements)
+            for tag, align in (("", 16), ("packed_", 1), ("large_blocks_first_", 16)):
                 displs, ext = gen.packed_displacements(sizes, align)
+                if tag == "large_blocks_first_":
+                    at = 0
+                    for i in sorted(range(len(sizes)), key=lambda i: -sizes[i]):
+                        displs[i] = at
+                        at += -(-sizes[i] // 16) * 16
                 isend = torch.empty((p, ext), dtype=torch.uint8, device=dev).fill_(3)
                 irecv = torch.empty((p, ext), dtype=torch.uint8, device=dev)
                 for name, alg in (("combined", iso.ISO_ALG_COMBINED), ("combined_bydim", iso.ISO_ALG_COMBINED_BYDIM),
