@@ -203,3 +203,57 @@ def test_stencil_sized_alltoallv_at_scale(alg):
     info = iso.iso_request_info(req)
     assert info["delivered_bytes"] == p * sum(sizes)
     iso.iso_request_free(req)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_sizes_with_ranks_in_groups(seed):
+    """Shift rounds of irregular blocks take the ranks in groups of 128 with the units of a group
+    entry by entry, the ranks left over one by one.  Seeded tori of 128 to about 2000 ranks (whole
+    groups only, groups and a rest, one group), random neighbourhoods with repeats and the zero
+    vector, block sizes of every unit width side by side (empty, 1 byte ... several KiB, with and
+    without an overlapping last unit), random gaps between the blocks; every byte, the three
+    schedules that use shift rounds."""
+    rng = np.random.default_rng(9000 + seed)
+    for _ in range(10000):
+        dims = tuple(int(x) for x in rng.integers(2, 14, size=int(rng.integers(2, 5))))
+        p = int(np.prod(dims))
+        if 128 <= p <= 2000:
+            break
+    else:
+        raise AssertionError("no torus drawn")
+    if seed == 0:
+        dims, p = (16, 8), 128                      # exactly one group
+    if seed == 1:
+        dims, p = (8, 8, 6), 384                    # whole groups only
+    s = int(rng.integers(3, 13))
+    offsets = [tuple(int(x) for x in rng.integers(-3, 4, size=len(dims))) for _ in range(s)]
+    offsets[s // 2] = (0,) * len(dims)
+    offsets[-1] = offsets[0]
+    choices = [0, 1, 2, 3, 4, 5, 8, 15, 16, 17, 33, 64, 100, 1024, 1030, 4096, 5000]
+    sizes = [int(x) for x in rng.choice(choices, size=s)]
+    sizes[0] = 4096
+    sizes[1] = 1
+    sd, at = [], int(rng.integers(0, 9))
+    for sz in sizes:
+        sd.append(at)
+        at += sz + int(rng.integers(0, 20))
+    sext = at + 3
+    rd, at = [0] * s, 0
+    for i in rng.permutation(s):
+        rd[int(i)] = at
+        at += sizes[int(i)] + int(rng.integers(0, 7))
+    rext = at + 1
+    send_h = rng.integers(0, 256, size=(p, sext), dtype=np.uint8)
+    want = orc.alltoallv(dims, offsets, send_h, sizes, sd, np.full((p, rext), 0xEE, np.uint8), rd)
+    comm = _comm(dims, offsets)
+    send = torch.from_numpy(send_h).to(DEV)
+    for alg in (iso.ISO_ALG_COMBINED, iso.ISO_ALG_COMBINED_BYDIM, iso.ISO_ALG_ONEHOP):
+        recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+        wsb = iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes)
+        work = torch.full((max(wsb, 16),), 0xDD, dtype=torch.uint8, device=DEV)
+        req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm, alg)
+        iso.iso_start(req)
+        iso.iso_wait(req)
+        assert np.array_equal(recv.cpu().numpy(), want), f"dims={dims} sizes={sizes} alg={ALG_NAMES[alg]}"
+        iso.iso_request_free(req)
+    assert np.array_equal(send.cpu().numpy(), send_h)
