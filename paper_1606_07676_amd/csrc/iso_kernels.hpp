@@ -249,6 +249,12 @@ __device__ __forceinline__ void fetch_now(const ShiftArgs &a) {
 
 template <typename V, bool LDS, bool NTL, bool TAIL, bool GROUPS = false>
 __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a) {
+    fetch_now(a);
+    if constexpr (GROUPS) {
+        asm volatile("" ::"s"(a.group), "s"(a.grouped));
+        fetch_now(a.d_group_k);
+        fetch_now(a.d_group);
+    }
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
     uint32_t tile;
@@ -326,8 +332,23 @@ __global__ __launch_bounds__(kThreads) void shift_round_uniform_kernel(const Shi
     move_unit<vec16_t, NTL>(dst, src, (uint64_t)(ch0 + (threadIdx.x & 63u)) * sizeof(vec16_t));
 }
 
+// (the decode constants of the first three dimensions with the rest: few tori have more, and each
+// further dimension's are fetched where the decode reaches it)
+__device__ __forceinline__ void fetch_now(const VectorArgs &a) {
+    asm volatile("" ::"s"(a.entries), "s"(a.offsets), "s"(a.map.n_tiles), "s"(a.map.run_log2), "s"(a.map.per_xcd),
+                 "s"(a.total), "s"(a.k), "s"(a.d), "s"(a.entry_major), "s"(a.inner[0]), "s"(a.inner[1]),
+                 "s"(a.inner[2]));
+    fetch_now(a.d_chunks);
+    fetch_now(a.d_k);
+    fetch_now(a.d_p);
+    fetch_now(a.d_dims[0]);
+    fetch_now(a.d_dims[1]);
+    fetch_now(a.d_dims[2]);
+}
+
 template <typename V, bool LDS, bool TAIL>
 __global__ __launch_bounds__(kThreads) void vector_round_kernel(const VectorArgs a) {
+    fetch_now(a);
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     const EntryTable<LDS> table(a.entries, a.k, lds);
     uint32_t tile;
@@ -477,8 +498,21 @@ __device__ __forceinline__ bool mesh_source_rank(const Args &a, const DevEntry &
 // groups of 8 ranks -4 % of the step, 32 -5 %, 64 -6.5 %, 128 and 256 -7.5 %, 1024 -7 %.)
 constexpr uint32_t kBlockGroupLog2 = 7, kBlockGroup = 1u << kBlockGroupLog2;
 
+__device__ __forceinline__ void fetch_now(const BlockArgs &a) {
+    asm volatile("" ::"s"(a.entries), "s"(a.prefix), "s"(a.map.n_tiles), "s"(a.map.run_log2), "s"(a.map.per_xcd),
+                 "s"(a.total), "s"(a.k), "s"(a.vector_round), "s"(a.inner), "s"(a.pj), "s"(a.equal_units),
+                 "s"(a.entry_major), "s"(a.grouped));
+    fetch_now(a.d_row);
+    fetch_now(a.d_inner);
+    fetch_now(a.d_pj);
+    fetch_now(a.d_units);
+    fetch_now(a.d_plane);
+    fetch_now(a.d_group_row);
+}
+
 template <bool LDS, bool MESH, bool NTL, bool GROUPS = false>
 __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a) {
+    if constexpr (!MESH) fetch_now(a);
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
     __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
     const uint32_t *prefix = a.prefix;
