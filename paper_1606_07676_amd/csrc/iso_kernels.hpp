@@ -517,7 +517,9 @@ __global__ __launch_bounds__(kThreads) void block_round_kernel(const BlockArgs a
     __shared__ uint32_t lds_prefix[LDS ? 2 * kLdsEntries + 1 : 1];
     const uint32_t *prefix = a.prefix;
     if constexpr (LDS) {
-        for (uint32_t q = threadIdx.x; q <= 2 * a.k; q += kThreads) lds_prefix[q] = a.prefix[q];
+        // staged by the workgroup's last lanes, the entries (below) by its first: with few entries these are
+        // different wavefronts, and the two loads are in flight together
+        for (uint32_t q = kThreads - 1 - threadIdx.x; q <= 2 * a.k; q += kThreads) lds_prefix[q] = a.prefix[q];
         prefix = lds_prefix;
     }
     const EntryTable<LDS> table(a.entries, a.k, lds);     // synchronises the workgroup when LDS
