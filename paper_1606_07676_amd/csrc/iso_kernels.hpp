@@ -256,11 +256,20 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
         fetch_now(a.d_group);
     }
     __shared__ DevEntry lds[LDS ? kLdsEntries : 1];
-    const EntryTable<LDS> table(a.entries, a.k, lds);
     uint32_t tile;
-    if (!tile_of_block(a.map, tile)) return;
+    if (!tile_of_block(a.map, tile)) return;            // (the whole workgroup: no one is left at the barrier)
+    // The table goes through LDS; its load is under way while the lanes work out their indices, which do
+    // not depend on it.
+    static_assert(sizeof(DevEntry) == 48, "staged as three 16-byte words");
+    vec16_t staged0 = {}, staged1 = {}, staged2 = {};   // (plain registers: a struct here ends up in LDS itself)
+    const bool stages = LDS && threadIdx.x < a.k;
+    if (stages) {
+        const vec16_t *from = (const vec16_t *)(a.entries + threadIdx.x);
+        staged0 = from[0];
+        staged1 = from[1];
+        staged2 = from[2];
+    }
     const uint32_t u = tile * (uint32_t)kThreads + threadIdx.x;
-    if (u >= a.total) return;
     uint32_t t, ch, R, e;
     fast_divmod(u, a.d_chunks, t, ch);
     if constexpr (GROUPS) {                             // an instantiation of its own: the few scalar loads and
@@ -280,7 +289,17 @@ __global__ __launch_bounds__(kThreads) void shift_round_kernel(const ShiftArgs a
     }
     const uint32_t q = fast_div(R, a.d_inner);
     const uint32_t rj = q - fast_div(q, a.d_pj) * a.pj;       // coordinate of R in the shifted dimension
-    const DevEntry en = table[e];
+    if constexpr (LDS) {
+        if (stages) {
+            vec16_t *to = (vec16_t *)(lds + threadIdx.x);
+            to[0] = staged0;
+            to[1] = staged1;
+            to[2] = staged2;
+        }
+        __syncthreads();
+    }
+    if (u >= a.total) return;                                  // (indices beyond the launch are never used)
+    const DevEntry en = LDS ? lds[e] : a.entries[e];
     // v steps back along the dimension, around the ring where that passes coordinate 0 (modulo 2^32;
     // the true result lies in [0, p))
     uint32_t srcR = R - en.shift * a.inner;
