@@ -694,8 +694,19 @@ struct StagedRoundArgs {
     FastDiv d_upb, d_row, d_plane, d_inner, d_pj;   // upb; k_rows * upb; ranks * upb
 };
 
+__device__ __forceinline__ void fetch_now(const StagedRoundArgs &a) {
+    asm volatile("" ::"s"(a.entries), "s"(a.map.n_tiles), "s"(a.map.run_log2), "s"(a.map.per_xcd), "s"(a.p), "s"(a.k),
+                 "s"(a.k_rows), "s"(a.ranks), "s"(a.upb), "s"(a.inner), "s"(a.pj));
+    fetch_now(a.d_upb);
+    fetch_now(a.d_row);
+    fetch_now(a.d_plane);
+    fetch_now(a.d_inner);
+    fetch_now(a.d_pj);
+}
+
 template <typename V, bool NTL, uint32_t UPL>
 __global__ __launch_bounds__(kThreads) void staged_round_kernel(const StagedRoundArgs a) {
+    fetch_now(a);
     __shared__ DevEntry lds[kLdsEntries];
     extern __shared__ __align__(16) unsigned char tile_bytes[];
     V *tile = (V *)tile_bytes;
@@ -786,8 +797,18 @@ struct DeliverArgs {
     FastDiv d_upb, d_rows, d_plane, d_row;    // upb; k_rows * upb; ranks * upb; s * upb
 };
 
+__device__ __forceinline__ void fetch_now(const DeliverArgs &a) {
+    asm volatile("" ::"s"(a.entries), "s"(a.dst), "s"(a.map.n_tiles), "s"(a.map.run_log2), "s"(a.map.per_xcd), "s"(a.p),
+                 "s"(a.s), "s"(a.k_rows), "s"(a.ranks), "s"(a.upb));
+    fetch_now(a.d_upb);
+    fetch_now(a.d_rows);
+    fetch_now(a.d_plane);
+    fetch_now(a.d_row);
+}
+
 template <typename V, bool NTL, uint32_t UPL>
 __global__ __launch_bounds__(kThreads) void deliver_kernel(const DeliverArgs a) {
+    fetch_now(a);
     __shared__ DeliverEntry lds[kLdsEntries];
     extern __shared__ __align__(16) unsigned char tile_bytes[];
     V *tile = (V *)tile_bytes;
