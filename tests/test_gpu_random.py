@@ -191,3 +191,72 @@ def _irregular_body(rng, mesh, dims, periodic, offsets):
         iso.iso_request_free(req)
         assert np.array_equal(grecv.cpu().numpy(), gwant), ("allgatherv", dims, periodic, offsets, g, alg)
     assert np.array_equal(send.cpu().numpy(), send_h) and np.array_equal(psend.cpu().numpy(), psend_h)
+
+
+def test_many_seeded_tori_regular_and_irregular():
+    """A broad sweep in one test: 300 seeded tori (half of them with 128 to 20 000 ranks, so that
+    rank groups, leftover ranks and many tiles occur), random neighbourhoods, one regular block
+    size and one set of irregular sizes each, all six algorithms, both collectives; every byte
+    against the oracle."""
+    bad = []
+    for seed in range(300):
+        rng = np.random.default_rng(777000 + seed)
+        lo, hi = (128, 20000) if seed % 2 else (2, 5000)
+        for _ in range(10000):
+            dims = tuple(int(x) for x in rng.integers(1, 17, size=int(rng.integers(1, 6))))
+            p = int(np.prod(dims))
+            if lo <= p <= hi:
+                break
+        else:
+            raise AssertionError("no torus drawn")
+        d = len(dims)
+        s = int(rng.integers(1, 20))
+        offsets = [tuple(int(x) for x in rng.integers(-4, 5, size=d)) for _ in range(s)]
+        comm = iso.iso_neighborhood_create(dims, np.asarray(offsets, np.int32).reshape(s, d))
+        m = int(rng.choice([1, 3, 8, 16, 24, 48, 64, 100, 256, 1024, 2048, 4096, 4100]))
+        if p * s * m <= 32 << 20:
+            send_h = rng.integers(0, 256, size=(p, s, m), dtype=np.uint8)
+            one_h = rng.integers(0, 256, size=(p, m), dtype=np.uint8)
+            expected = {iso.ISO_OP_ALLTOALL: orc.alltoall(dims, offsets, send_h),
+                        iso.ISO_OP_ALLGATHER: orc.allgather(dims, offsets, one_h)}
+            source = {iso.ISO_OP_ALLTOALL: torch.from_numpy(send_h).to(DEV),
+                      iso.ISO_OP_ALLGATHER: torch.from_numpy(one_h).to(DEV)}
+            for alg in TORUS_ALGS:
+                for op in (iso.ISO_OP_ALLTOALL, iso.ISO_OP_ALLGATHER):
+                    recv = torch.full((p, s, m), 0xEE, dtype=torch.uint8, device=DEV)
+                    work = torch.empty(max(iso.iso_workspace_bytes(comm, op, alg, m), 16), dtype=torch.uint8,
+                                       device=DEV)
+                    init = (iso.iso_neighbor_alltoall_init if op == iso.ISO_OP_ALLTOALL
+                            else iso.iso_neighbor_allgather_init)
+                    req = init(source[op], recv, m, work, comm, alg)
+                    iso.iso_start(req)
+                    iso.iso_wait(req)
+                    if not np.array_equal(recv.cpu().numpy(), expected[op]):
+                        bad.append(("regular", seed, dims, s, m, alg, op))
+                    iso.iso_request_free(req)
+        sizes = [int(x) for x in rng.choice([0, 1, 2, 5, 8, 16, 17, 33, 64, 100, 1024, 1030, 4096], size=s)]
+        sd, at = [], int(rng.integers(0, 9))
+        for sz in sizes:
+            sd.append(at)
+            at += sz + int(rng.integers(0, 20))
+        sext = at + 3
+        rd, at = [0] * s, 0
+        for i in rng.permutation(s):
+            rd[int(i)] = at
+            at += sizes[int(i)] + int(rng.integers(0, 7))
+        rext = at + 1
+        if p * max(sext, rext) <= 32 << 20:
+            send_h = rng.integers(0, 256, size=(p, sext), dtype=np.uint8)
+            want = orc.alltoallv(dims, offsets, send_h, sizes, sd, np.full((p, rext), 0xEE, np.uint8), rd)
+            send = torch.from_numpy(send_h).to(DEV)
+            for alg in TORUS_ALGS:
+                recv = torch.full((p, rext), 0xEE, dtype=torch.uint8, device=DEV)
+                work = torch.empty(max(iso.iso_workspace_bytes_v(comm, iso.ISO_OP_ALLTOALL, alg, sizes), 16),
+                                   dtype=torch.uint8, device=DEV)
+                req = iso.iso_neighbor_alltoallv_init(send, sizes, sd, sext, recv, sizes, rd, rext, work, comm, alg)
+                iso.iso_start(req)
+                iso.iso_wait(req)
+                if not np.array_equal(recv.cpu().numpy(), want):
+                    bad.append(("irregular", seed, dims, sizes, alg))
+                iso.iso_request_free(req)
+    assert not bad, bad[:5]
